@@ -1,0 +1,107 @@
+"""ctypes binding of the CPU oracle (oracle/gemm_ref.c).  Test infrastructure.
+
+All functions take 2-D float64 NumPy arrays whose last axis is contiguous; the
+leading dimension is taken from the row stride, so padded views (a[:, :K] of
+a wider buffer) are passed without copying and their padding is never touched.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            path = _build.build()
+        lib = ctypes.CDLL(path)
+        i64, dp = ctypes.c_int64, ctypes.c_void_p
+        for name in ("gemm_f64_ref", "gemm_f64_ref_ijk", "gemm_f64_absref"):
+            fn = getattr(lib, name)
+            fn.argtypes = [i64, i64, i64, dp, i64, dp, i64, dp, i64]
+            fn.restype = ctypes.c_int
+        lib.gemm_f64_ref_threads.restype = ctypes.c_int
+        lib.gemm_f64_ref_set_threads.argtypes = [ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def _ld(x: np.ndarray) -> int:
+    assert x.dtype == np.float64 and x.ndim == 2
+    if x.size == 0:
+        # no element is touched; any legal leading dimension will do
+        return max(1, x.shape[1], x.strides[0] // 8 if x.strides[0] % 8 == 0 else 1)
+    if x.shape[1] > 1:
+        assert x.strides[1] == 8, "last axis must be contiguous"
+    if x.shape[0] > 1:
+        assert x.strides[0] % 8 == 0 and x.strides[0] > 0
+        return x.strides[0] // 8
+    return max(1, x.shape[1])
+
+
+def _call(name, A, B, C, lda=None, ldb=None, ldc=None):
+    M, K = A.shape
+    K2, N = B.shape
+    assert K2 == K and C.shape == (M, N)
+    assert C.flags.writeable
+    fn = getattr(_load(), name)
+    rc = fn(M, N, K, A.ctypes.data, lda or _ld(A), B.ctypes.data, ldb or _ld(B),
+            C.ctypes.data, ldc or _ld(C))
+    if rc != 0:
+        raise ValueError("%s failed with code %d" % (name, rc))
+    return C
+
+
+def gemm_f64_ref(A, B, C):
+    """C += A @ B, the definition (Section 2.1 loop nest), in place; returns C."""
+    return _call("gemm_f64_ref", A, B, C)
+
+
+def gemm_f64_ref_ijk(A, B, C):
+    """Same result through the literal i-j-k nest (serial, slow)."""
+    return _call("gemm_f64_ref_ijk", A, B, C)
+
+
+def gemm_f64_absref(A, B, C):
+    """C += |A| @ |B| by the same loop; with C = 0 gives the tolerance scale S."""
+    return _call("gemm_f64_absref", A, B, C)
+
+
+def raw(name):
+    """The raw C entry point (for argument-validation tests)."""
+    return getattr(_load(), name)
+
+
+def ref_threads() -> int:
+    return int(_load().gemm_f64_ref_threads())
+
+
+def set_ref_threads(n: int) -> None:
+    _load().gemm_f64_ref_set_threads(int(n))
+
+
+def ref_rows(A, B, C0, rows):
+    """Oracle result for selected rows only: out[r] = C0[rows[r]] + A[rows[r]] @ B.
+
+    Row i of the result depends on row i of A and of C alone, so the selected
+    rows are gathered into compact arrays and the same oracle routine is run on
+    them; nothing else is computed.
+    """
+    rows = np.asarray(rows, dtype=np.int64)
+    Ar = np.ascontiguousarray(A[rows, :])
+    Cr = np.ascontiguousarray(C0[rows, :])
+    return gemm_f64_ref(Ar, B, Cr)
+
+
+def abs_rows(A, B, rows):
+    """Tolerance scale S[r, j] = sum_k |A[rows[r], k] * B[k, j]| for selected rows."""
+    rows = np.asarray(rows, dtype=np.int64)
+    Ar = np.ascontiguousarray(A[rows, :])
+    S = np.zeros((len(rows), B.shape[1]), dtype=np.float64)
+    return gemm_f64_absref(Ar, B, S)
