@@ -1,0 +1,126 @@
+/*
+ * gemm_f64.h -- C ABI of libgemm_f64.so: double-precision GEMM for AMD MI355X (gfx950).
+ *
+ * The operation is the one the paper optimises (Section 2.1 "Affine Ops": the
+ * canonical i, j, k nest  C[i][j] = C[i][j] + A[i][k] * B[k][j]  on three
+ * row-major f64 buffers, C read and written in place; Section 2.2: the identity
+ * layout map is row-major; Section 2.15 Q4: alpha = beta = 1 are assumed and
+ * strides are the only layout generality kept):
+ *
+ *      C[i*ldc + j] += sum_{k=0}^{K-1} A[i*lda + k] * B[k*ldb + j],   0 <= i < M, 0 <= j < N.
+ *
+ * All matrix pointers are DEVICE pointers; leading dimensions count elements.
+ * Every step of the computation runs in this library's own HIP kernels
+ * (FP64 MFMA accumulator tiles, A/B panels staged through LDS, explicit edge
+ * tiles); there is no host fallback and no dependency on a BLAS library.
+ */
+#ifndef GEMM_F64_H
+#define GEMM_F64_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Return codes (0 = success; on any error nothing has been launched). */
+enum {
+    GEMM_F64_OK = 0,
+    GEMM_F64_ERR_DIM = -1,       /* M, N or K negative                                   */
+    GEMM_F64_ERR_LDA = -2,       /* lda < max(1, K)                                      */
+    GEMM_F64_ERR_LDB = -3,       /* ldb < max(1, N)                                      */
+    GEMM_F64_ERR_LDC = -4,       /* ldc < max(1, N)                                      */
+    GEMM_F64_ERR_NULL = -5,      /* null pointer for an operand that has elements        */
+    GEMM_F64_ERR_ALIGN = -6,     /* a pointer is not 8-byte aligned                      */
+    GEMM_F64_ERR_LAUNCH = -7,    /* the HIP runtime refused the launch (see hipGetLastError) */
+    GEMM_F64_ERR_TOO_LARGE = -8, /* M, N or K above 2^31 - 1                             */
+    GEMM_F64_ERR_VARIANT = -9    /* unknown kernel variant index                         */
+};
+
+/*
+ * gemm_f64: enqueue C += A * B on `stream` and return at once (asynchronous).
+ *
+ *   M, N, K   logical sizes: A is M x K, B is K x N, C is M x N.  Zero is allowed:
+ *             M == 0 or N == 0 does nothing; K == 0 leaves C unchanged.
+ *   A, lda    device pointer, row-major, element (i,k) at A[i*lda + k]; lda >= max(1,K).
+ *   B, ldb    device pointer, row-major, element (k,j) at B[k*ldb + j]; ldb >= max(1,N).
+ *   C, ldc    device pointer, row-major, element (i,j) at C[i*ldc + j]; ldc >= max(1,N);
+ *             read and written in place.
+ *   stream    a hipStream_t passed as void*; NULL means the default stream.
+ *
+ * Layout and ownership: the caller owns all three buffers; the library keeps no
+ * pointer, allocates nothing, uses no workspace and has no global state, so it
+ * may be called from several host threads.  Inside a row's ld span, elements at
+ * column index >= the logical width (K for A, N for B and C) are never read and
+ * never written, and nothing past the last logical element of the last row is
+ * touched.  C must not overlap A or B; A and B may alias each other.
+ *
+ * Alignment: pointers must be 8-byte aligned.  When A and B are 16-byte aligned
+ * and lda, ldb are even the panels are fetched with 128-bit loads; otherwise a
+ * 64-bit-load variant of the same kernel is used (same result, slower).
+ *
+ * Arithmetic: binary64 throughout.  Products are accumulated from zero in the
+ * matrix unit, four k at a time, and C is added once at the end, so the
+ * rounding differs from the sequential nest: results are bit-identical to it
+ * whenever every partial sum is exact (e.g. small-integer data) and within
+ * 1e-13 * sum_k |a_ik * b_kj| elementwise otherwise.  The zero padding the
+ * kernel uses for ragged K is applied to both operands, so a live Inf or NaN
+ * never meets a padded zero.
+ *
+ * Errors: a negative code from the enum above; no exception, no errno.
+ */
+int gemm_f64(int64_t M, int64_t N, int64_t K,
+             const double *A, int64_t lda,
+             const double *B, int64_t ldb,
+             double *C, int64_t ldc,
+             void *stream);
+
+/*
+ * gemm_f64_ex: the same operation with the kernel variant chosen by the caller
+ * (Section 2.10 of the paper tunes M_C, K_C, M_R, N_R by hand per problem; here
+ * the analogous parameters are the workgroup macro-tile and the wave tile).
+ * variant == -1 selects automatically, exactly as gemm_f64 does.  Variant
+ * indices run from 0 to gemm_f64_variant_count() - 1.
+ */
+int gemm_f64_ex(int64_t M, int64_t N, int64_t K,
+                const double *A, int64_t lda,
+                const double *B, int64_t ldb,
+                double *C, int64_t ldc,
+                void *stream, int variant);
+
+/* Number of kernel variants and their names ("mfma_128x128x16", ...; NULL if out of range). */
+int gemm_f64_variant_count(void);
+const char *gemm_f64_variant_name(int variant);
+
+/*
+ * gemm_f64_choose_variant: the pure host-side selection rule used when
+ * variant == -1 (the paper's Section 2.15 Q5 asks how parameters are to be
+ * determined; this is a small analytical model over tile quantisation).
+ * num_cu is the number of compute units of the target device (256 on MI355X).
+ * Touches no device.
+ */
+int gemm_f64_choose_variant(int64_t M, int64_t N, int64_t K, int num_cu);
+
+/*
+ * gemm_f64_tile_of_block: the workgroup-id -> C-tile mapping used by the MFMA
+ * kernels (the stand-in for the cache-level loop order of the paper's Section
+ * 2.4 schedule).  Workgroups are handed to the 8 XCDs round-robin, so block b
+ * runs on XCD b % 8; the mapping gives each XCD a contiguous run of a
+ * grouped tile order so that tiles resident on one XCD share A and B panels
+ * in that XCD's L2.  Pure host function; writes the tile coordinates of
+ * `block` to *tile_m and *tile_n; returns 0, or GEMM_F64_ERR_DIM if the
+ * arguments are out of range.
+ */
+int gemm_f64_tile_of_block(int64_t block, int64_t tiles_m, int64_t tiles_n,
+                           int64_t *tile_m, int64_t *tile_n);
+
+/* Static description of a return code; never NULL, never freed. */
+const char *gemm_f64_strerror(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int gemm_f64_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GEMM_F64_H */

@@ -1,0 +1,122 @@
+"""Thin ctypes binding of libgemm_f64.so (see include/gemm_f64.h).
+
+Argument marshalling only: every function forwards to the C entry point of the
+same name.  Device buffers may be given as torch tensors (their data_ptr is
+used) or as integer addresses.  There is no fallback of any kind: if the
+library has not been built, loading raises.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgemm_f64.so")
+
+_lib = None
+
+
+class GemmF64Error(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("gemm_f64 error %d: %s" % (code, text))
+        self.code = code
+
+
+def load():
+    """Load libgemm_f64.so; raises if it is missing (build it with __graft_entry__.build())."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s not found: the HIP library is not built (run `python -c 'import __graft_entry__ as g; g.build()'`); "
+            "there is no CPU fallback" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    lib.gemm_f64.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
+    lib.gemm_f64.restype = ci
+    lib.gemm_f64_ex.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, ci]
+    lib.gemm_f64_ex.restype = ci
+    lib.gemm_f64_variant_count.argtypes = []
+    lib.gemm_f64_variant_count.restype = ci
+    lib.gemm_f64_variant_name.argtypes = [ci]
+    lib.gemm_f64_variant_name.restype = ctypes.c_char_p
+    lib.gemm_f64_choose_variant.argtypes = [i64, i64, i64, ci]
+    lib.gemm_f64_choose_variant.restype = ci
+    lib.gemm_f64_tile_of_block.argtypes = [i64, i64, i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.gemm_f64_tile_of_block.restype = ci
+    lib.gemm_f64_strerror.argtypes = [ci]
+    lib.gemm_f64_strerror.restype = ctypes.c_char_p
+    lib.gemm_f64_version.argtypes = []
+    lib.gemm_f64_version.restype = ci
+    _lib = lib
+    return lib
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def gemm_f64_strerror(code: int) -> str:
+    return load().gemm_f64_strerror(int(code)).decode()
+
+
+def _check(code):
+    if code != 0:
+        raise GemmF64Error(code, gemm_f64_strerror(code))
+
+
+def gemm_f64(M, N, K, A, lda, B, ldb, C, ldc, stream=None):
+    """Enqueue C += A @ B (device pointers, row-major, leading dimensions in elements)."""
+    _check(load().gemm_f64(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _stream(stream)))
+
+
+def gemm_f64_ex(M, N, K, A, lda, B, ldb, C, ldc, stream=None, variant=-1):
+    """Same, with an explicit kernel variant (-1 = automatic)."""
+    _check(load().gemm_f64_ex(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _stream(stream), int(variant)))
+
+
+def gemm_f64_raw(M, N, K, A, lda, B, ldb, C, ldc, stream=0, variant=-1) -> int:
+    """Return the raw status code instead of raising (for error-path tests)."""
+    return int(load().gemm_f64_ex(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, stream, int(variant)))
+
+
+def gemm_f64_variant_count() -> int:
+    return int(load().gemm_f64_variant_count())
+
+
+def gemm_f64_variant_name(variant: int):
+    s = load().gemm_f64_variant_name(int(variant))
+    return None if s is None else s.decode()
+
+
+def gemm_f64_choose_variant(M, N, K, num_cu=256) -> int:
+    return int(load().gemm_f64_choose_variant(M, N, K, int(num_cu)))
+
+
+def gemm_f64_tile_of_block(block, tiles_m, tiles_n):
+    tm, tn = ctypes.c_int64(-1), ctypes.c_int64(-1)
+    _check(load().gemm_f64_tile_of_block(block, tiles_m, tiles_n, ctypes.byref(tm), ctypes.byref(tn)))
+    return int(tm.value), int(tn.value)
+
+
+def gemm_f64_version() -> int:
+    return int(load().gemm_f64_version())
+
+
+def variant_index(name: str) -> int:
+    for v in range(gemm_f64_variant_count()):
+        if gemm_f64_variant_name(v) == name:
+            return v
+    raise KeyError(name)

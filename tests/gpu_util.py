@@ -1,0 +1,74 @@
+"""Helpers for the GPU parity tests: move padded host buffers to the device, call the C ABI, compare."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2003_00532_amd import binding, synth
+
+TOL = 1e-13  # |C - C_ref| <= TOL * sum_k |a_ik b_kj|, the bar set for this path
+
+
+def to_dev(buf, dev="cuda:0"):
+    return torch.from_numpy(np.ascontiguousarray(buf)).to(dev)
+
+
+def run_device(Abuf, Bbuf, Cbuf, M, N, K, variant=-1, stream=None):
+    """Copy padded (rows, ld) host buffers to the GPU, run C += A B there, return (A, B, C) device buffers as NumPy."""
+    lda, ldb, ldc = Abuf.shape[1], Bbuf.shape[1], Cbuf.shape[1]
+    dA, dB, dC = to_dev(Abuf), to_dev(Bbuf), to_dev(Cbuf)
+    binding.gemm_f64_ex(M, N, K, dA, lda, dB, ldb, dC, ldc, stream=stream, variant=variant)
+    torch.cuda.synchronize()
+    return dA.cpu().numpy(), dB.cpu().numpy(), dC.cpu().numpy()
+
+
+def make_impl(variant=-1, force_ld=None):
+    """Adapter with the `impl(A, B, C)` signature of tests/pins.py that runs on the GPU.
+
+    Each operand is placed in a fresh sentinel-filled (rows, ld) device buffer whose ld is the
+    view's row stride (so padded and odd leading dimensions reach the kernel); after the call the
+    device-side padding of all three buffers must still hold the sentinel.
+    """
+    def ld_of(x):
+        if x.shape[0] > 1 and x.size > 0 and x.strides[0] % 8 == 0 and x.strides[0] // 8 >= x.shape[1]:
+            return max(1, x.strides[0] // 8)
+        return max(1, x.shape[1])
+
+    def impl(A, B, C):
+        M, K = A.shape
+        N = B.shape[1]
+        bufs = []
+        for x in (A, B, C):
+            ld = ld_of(x) if force_ld is None else max(1, x.shape[1]) + force_ld
+            b = synth.padded(x.shape[0], x.shape[1], ld)
+            b[:, :x.shape[1]] = x
+            bufs.append(b)
+        a2, b2, c2 = run_device(bufs[0], bufs[1], bufs[2], M, N, K, variant=variant)
+        assert synth.padding_intact(a2, K) and synth.padding_intact(b2, N) and synth.padding_intact(c2, N), \
+            "device padding was written"
+        C[...] = c2[:, :N]
+    return impl
+
+
+def check_tolerance(got, want, S, what=""):
+    """Elementwise |got - want| <= TOL * S; exact equality where S == 0.  Returns the worst ratio."""
+    assert not np.isnan(got).any(), what + ": NaN in result"
+    diff = np.abs(got - want)
+    zero = S == 0
+    if zero.any():
+        assert np.all(diff[zero] == 0), what + ": mismatch where the scale is zero"
+    ratio = np.max(diff[~zero] / S[~zero]) if (~zero).any() else 0.0
+    assert ratio <= TOL, "%s: max |diff|/S = %.3g exceeds %.1g" % (what, ratio, TOL)
+    return float(ratio)
+
+
+def check_against_oracle(A, B, C0, got, integer, what=""):
+    want = C0.copy()
+    oracle.gemm_f64_ref(A, B, want)
+    if integer:
+        bad = np.flatnonzero(got.view(np.uint64).ravel() != want.view(np.uint64).ravel())
+        assert bad.size == 0, "%s: %d elements differ bitwise (first flat index %d: got %r want %r)" % (
+            what, bad.size, bad[0], got.ravel()[bad[0]], want.ravel()[bad[0]])
+        return 0.0
+    S = np.zeros_like(want)
+    oracle.gemm_f64_absref(A, B, S)
+    return check_tolerance(got, want, S, what)

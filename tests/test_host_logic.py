@@ -1,0 +1,116 @@
+"""Host-side logic of libgemm_f64.so that needs no GPU: exported symbols, argument validation,
+variant selection and the workgroup -> tile mapping."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2003_00532_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if fn.endswith(".h"):
+            text = open(os.path.join(inc, fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names += re.findall(r"\b(gemm_f64\w*)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    names = declared_functions()
+    assert "gemm_f64" in names and "gemm_f64_ex" in names and len(names) >= 8
+    for n in names:
+        assert hasattr(lib, n), "libgemm_f64.so does not export " + n
+    for n in names:
+        assert hasattr(binding, n) or hasattr(binding.load(), n)
+
+
+def test_version_and_variant_table():
+    assert binding.gemm_f64_version() >= 100
+    n = binding.gemm_f64_variant_count()
+    names = [binding.gemm_f64_variant_name(v) for v in range(n)]
+    assert names[0] == "naive" and len(set(names)) == n
+    assert binding.gemm_f64_variant_name(n) is None and binding.gemm_f64_variant_name(-1) is None
+
+
+def test_argument_validation_happens_before_any_launch():
+    # every rejected call returns before the device is touched, so this runs without a GPU;
+    # 0x1000 is a fake, suitably aligned, non-null address that is never dereferenced
+    p = 0x1000
+    raw = binding.gemm_f64_raw
+    assert raw(-1, 2, 2, p, 2, p, 2, p, 2) == -1
+    assert raw(2, -1, 2, p, 2, p, 2, p, 2) == -1
+    assert raw(2, 2, -1, p, 2, p, 2, p, 2) == -1
+    assert raw(2, 2, 3, p, 2, p, 2, p, 2) == -2
+    assert raw(2, 3, 2, p, 2, p, 2, p, 3) == -3
+    assert raw(2, 3, 2, p, 2, p, 3, p, 2) == -4
+    assert raw(2, 2, 2, None, 2, p, 2, p, 2) == -5
+    assert raw(2, 2, 2, p, 2, None, 2, p, 2) == -5
+    assert raw(2, 2, 2, p, 2, p, 2, None, 2) == -5
+    assert raw(2, 2, 2, p + 4, 2, p, 2, p, 2) == -6
+    assert raw(2, 2, 2, p, 2, p, 2, p + 2, 2) == -6
+    assert raw(2 ** 31, 2, 2, p, 2, p, 2, p, 2) == -8
+    assert raw(2, 2, 2, p, 2, p, 2, p, 2, variant=99) == -9
+    # empty problems succeed without touching anything, even with null pointers
+    assert raw(0, 5, 5, None, 5, None, 5, None, 5) == 0
+    assert raw(5, 0, 5, None, 5, None, 1, None, 1) == 0
+    assert raw(5, 5, 0, None, 1, None, 5, p, 5) == 0
+    for code in range(-9, 1):
+        assert "unknown error" not in binding.gemm_f64_strerror(code)
+    assert "unknown" in binding.gemm_f64_strerror(-1234)
+    with pytest.raises(binding.GemmF64Error):
+        binding.gemm_f64_ex(2, 2, 3, p, 2, p, 2, p, 2, stream=0)
+
+
+@pytest.mark.parametrize("tiles", [(1, 1), (1, 9), (9, 1), (3, 5), (8, 8), (16, 16), (17, 17), (33, 7),
+                                   (64, 64), (5, 100), (100, 5), (13, 29)])
+def test_tile_mapping_is_a_bijection(tiles):
+    tm, tn = tiles
+    seen = set()
+    for b in range(tm * tn):
+        t = binding.gemm_f64_tile_of_block(b, tm, tn)
+        assert 0 <= t[0] < tm and 0 <= t[1] < tn
+        seen.add(t)
+    assert len(seen) == tm * tn
+    with pytest.raises(binding.GemmF64Error):
+        binding.gemm_f64_tile_of_block(tm * tn, tm, tn)
+
+
+def test_tile_mapping_keeps_an_xcd_compact():
+    # 64x64 tiles (8192^2 at 128x128): the first 64 workgroups of each XCD (two per compute unit,
+    # 32 compute units) must form an 8x8 patch, i.e. share 8 A panels and 8 B panels
+    tm = tn = 64
+    for xcd in range(8):
+        tiles = [binding.gemm_f64_tile_of_block(xcd + 8 * s, tm, tn) for s in range(64)]
+        rows = {t[0] for t in tiles}
+        cols = {t[1] for t in tiles}
+        assert len(rows) <= 8 and len(cols) <= 9
+
+
+def test_variant_selection_follows_tile_quantisation():
+    name = lambda M, N, K: binding.gemm_f64_variant_name(binding.gemm_f64_choose_variant(M, N, K, 256))
+    assert name(8192, 8192, 8192) == "mfma_128x128x16"
+    # 2088 x 2049 needs 289 tiles of 128x128, two rounds on 256 compute units at ~56 % use: a smaller tile wins
+    assert name(2088, 2049, 2047) != "mfma_128x128x16"
+    for (M, N, K) in [(1, 1, 1), (256, 256, 256), (2048, 2048, 2048), (16384, 16384, 256), (100000, 3, 7)]:
+        v = binding.gemm_f64_choose_variant(M, N, K, 256)
+        assert 1 <= v < binding.gemm_f64_variant_count()
+
+
+def test_gflops_convention_matches_the_papers_printed_numbers():
+    # GFLOPS = 2 M N K / t / 1e9 reproduces the figures printed next to the run times (Section 1.3)
+    path = os.path.join(ROOT, "tests", "golden", "paper_gflops_convention.txt")
+    for line in open(path):
+        if line.strip() and not line.startswith("#"):
+            name, M, N, K, secs, gflops = line.split()
+            got = 2.0 * int(M) * int(N) * int(K) / float(secs) / 1e9
+            assert abs(got - float(gflops)) < 0.006, (name, got)
+    w = synth.WORKLOADS["c3_8192"]
+    assert w.flops == 2.0 * 8192 ** 3 and w.algorithmic_bytes == 8.0 * 4 * 8192 ** 2
