@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the fp64 GEMM hot path on one MI355X.
+
+A step is one call of gemm_f64 (C += A B through the C ABI) on the named workload with A, B and C
+already resident in HBM.  Prints ONE JSON line on stdout: DGEMM GFLOP/s = 2 M N K / t / 1e9 (the
+paper's convention, Section 1.3), the roofline of the kernel (FP64 MFMA, 78.6 TFLOP/s published
+peak; per-launch duration measured with HIP events on the launch stream) and the CPU oracle timed on
+a bounded sample of the same workload.  Diagnostics go to stderr.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_8192] [--variant -1]
+    python bench.py --copy-calibration     # plain device copy of known size, for scaling rocprof counters
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP64_MFMA_TFLOPS = 78.6   # MI355X published dense FP64 matrix peak (256 CU x 128 flop/clk x 2.4 GHz)
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), scaled
+# by the copy-kernel calibration; None until measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(w, seed, target_seconds=12.0):
+    """Time the CPU oracle, as it stands, on complete rows of the same workload (all host threads)."""
+    import numpy as np
+    import oracle
+    from paper_2003_00532_amd import synth
+
+    threads = oracle.ref_threads()
+    _, B = synth.matrix(seed, synth.TAG_B, w.K, w.N, w.ldb, "uniform")
+
+    def run(rows):
+        A = np.empty((rows, w.K)); synth.fill(A, seed, synth.TAG_A, "uniform")
+        C = np.empty((rows, w.N)); synth.fill(C, seed, synth.TAG_C, "uniform" if w.c_kind == "uniform" else "zeros")
+        t0 = time.perf_counter()
+        oracle.gemm_f64_ref(A, B, C)
+        return time.perf_counter() - t0
+
+    pilot_rows = min(w.M, 4 * threads)
+    t_pilot = run(pilot_rows)
+    rows = int(pilot_rows * target_seconds / max(t_pilot, 1e-6))
+    rows = max(pilot_rows, min(w.M, (rows // threads) * threads))
+    t = run(rows)
+    gflops = 2.0 * rows * w.N * w.K / t / 1e9
+    return {"value": round(gflops, 3), "unit": "GFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": "first %d of %d rows of %s (N=%d, K=%d) in %.2f s; full-size time extrapolates to %.0f s"
+                      % (rows, w.M, w.name, w.N, w.K, t, t * w.M / rows)}
+
+
+def copy_calibration():
+    """A plain device-to-device copy of known size; run under rocprofv3 --pmc to scale FETCH_SIZE / WRITE_SIZE."""
+    import torch
+    n = 1 << 28  # 256 MiB read, 256 MiB written per copy
+    src = torch.empty(n, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "copies": 5}))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3_8192")
+    ap.add_argument("--variant", type=int, default=-1)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by row blocks "
+            "without collectives, see DESIGN.md, but no multi-GPU figure is produced)" % args.gpus)
+        sys.exit(2)
+
+    import torch
+    from paper_2003_00532_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the HIP path has no CPU fallback")
+        sys.exit(1)
+    binding.load()
+    if args.copy_calibration:
+        copy_calibration()
+        return
+
+    w = synth.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    t0 = time.perf_counter()
+    Ab, Bb, Cb = synth.workload_inputs(w, seed=args.seed)
+    dA, dB, dC = (torch.from_numpy(x).to(dev) for x in (Ab, Bb, Cb))
+    del Ab, Bb, Cb
+    torch.cuda.synchronize()
+    log("inputs for %s generated and resident in HBM after %.1f s" % (w.name, time.perf_counter() - t0))
+
+    props = torch.cuda.get_device_properties(0)
+    variant = args.variant if args.variant >= 0 else binding.gemm_f64_choose_variant(w.M, w.N, w.K, props.multi_processor_count)
+    vname = binding.gemm_f64_variant_name(variant)
+
+    stream = torch.cuda.current_stream()
+
+    def step():
+        binding.gemm_f64_ex(w.M, w.N, w.K, dA, w.lda, dB, w.ldb, dC, w.ldc, stream=stream, variant=args.variant)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # whole-job wall time over exactly `steps` steps, and per-launch durations from HIP events recorded
+    # on the launch stream (event i sits between launch i-1 and launch i)
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    events[0].record(stream)
+    for i in range(args.steps):
+        step()
+        events[i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_launch_ms = [events[i].elapsed_time(events[i + 1]) for i in range(args.steps)]
+    kernel_ms = sum(per_launch_ms) / len(per_launch_ms)
+
+    ms_per_step = wall * 1e3 / args.steps
+    gflops = w.flops / (ms_per_step * 1e-3) / 1e9
+    achieved_tflops = w.flops / (kernel_ms * 1e-3) / 1e12
+    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, vname))
+
+    out = {
+        "metric": "DGEMM GFLOP/s (2MNK/t), 1 GPU",
+        "value": round(gflops, 1),
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": "%s: fp64 row-major C += A*B, M=%d N=%d K=%d, lda=%d ldb=%d ldc=%d, A,B uniform[-1,1) seed %d, C %s"
+                               % (w.name, w.M, w.N, w.K, w.lda, w.ldb, w.ldc, args.seed, w.c_kind),
+                   "kernel_variant": vname, "device": props.name, "compute_units": props.multi_processor_count},
+        "pct_of_fp64_mfma_peak": round(100.0 * gflops / (PEAK_FP64_MFMA_TFLOPS * 1e3), 2),
+        "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": PEAK_FP64_MFMA_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_FP64_MFMA_TFLOPS, 4),
+                     "traffic": traffic, "kernel_ms": round(kernel_ms, 4),
+                     "kernel_ms_min": round(min(per_launch_ms), 4), "kernel_ms_max": round(max(per_launch_ms), 4),
+                     "algorithmic_flops_per_launch": w.flops, "algorithmic_bytes_per_launch": w.algorithmic_bytes},
+    }
+    if not args.no_cpu_baseline:
+        t0 = time.perf_counter()
+        out["cpu_baseline"] = cpu_baseline(w, args.seed)
+        log("cpu baseline took %.1f s" % (time.perf_counter() - t0))
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
