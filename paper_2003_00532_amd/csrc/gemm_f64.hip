@@ -140,7 +140,10 @@ extern "C" int gemm_f64_ex(int64_t M, int64_t N, int64_t K, const double *A, int
         variant = gemm_f64_choose_variant(M, N, K, cus);
     }
 
-    const bool vec = (((uintptr_t)A | (uintptr_t)B) & 15u) == 0 && (lda % 2 == 0) && (ldb % 2 == 0);
+    // 16-byte global->LDS loads need aligned operands; their per-lane byte offsets (up to 128 rows of
+    // A, 2 rows of B) are 32-bit, which bounds the leading dimensions.
+    const bool vec = (((uintptr_t)A | (uintptr_t)B) & 15u) == 0 && (lda % 2 == 0) && (ldb % 2 == 0) &&
+                     lda < (1 << 20) && ldb < (1 << 20);
     const int m = (int)M, n = (int)N, k = (int)K;
     hipError_t err = hipSuccess;
     switch (variant) {

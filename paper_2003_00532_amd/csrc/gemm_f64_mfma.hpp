@@ -23,6 +23,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace gemm_f64_detail {
 
 typedef double v4d __attribute__((ext_vector_type(4)));
@@ -69,36 +71,18 @@ __device__ __forceinline__ void stage_barrier()
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// The compiler cannot see an s_waitcnt inside an asm statement, and while an asynchronous
-// global->LDS load is in flight it answers every LDS dependency with a full lgkmcnt(0) drain, which
-// would expose the latency of the youngest fragment reads.  So the waits are placed by hand, at
-// points where only old reads are outstanding, and the fragment registers are passed through the
-// asm as read-write operands: afterwards the compiler regards them as complete.
-//   BARRIER = true : wait for everything (LDS reads and writes, global->LDS loads), then s_barrier;
-//   BARRIER = false: wait for outstanding LDS reads only.
-template <bool BARRIER, int NA_, int NB_>
-__device__ __forceinline__ void settle(v2d (&fa)[NA_], v2d (&fb)[NB_])
+// One asynchronous 16-byte-per-lane global->LDS load: lane l copies the 16 bytes at
+// sbase + voff(l) to LDS address lds_addr + 16 * l.  Issued as inline asm for two reasons: the
+// address is a wave-uniform 64-bit base in SGPRs plus a 32-bit per-lane offset, which costs no
+// vector ALU work when the base advances; and the compiler, which answers every LDS dependency
+// with a full lgkmcnt(0) drain while it knows such a load to be in flight, does not see it.
+// Completion is awaited by the s_waitcnt vmcnt(0) inside stage_barrier().
+__device__ __forceinline__ void async_copy16(uint32_t voff, const void *sbase, uint32_t lds_addr)
 {
-    static_assert((NA_ == 2 || NA_ == 4) && (NB_ == 2 || NB_ == 4), "two or four fragments per operand");
-    __builtin_amdgcn_sched_barrier(0);  // nothing, MFMAs included, is scheduled across
-#define GEMM_F64_SETTLE(...)                                                                              \
-    do {                                                                                                  \
-        if (BARRIER)                                                                                      \
-            asm volatile("s_waitcnt vmcnt(0) expcnt(0) lgkmcnt(0)\n\ts_barrier" : __VA_ARGS__::"memory"); \
-        else                                                                                              \
-            asm volatile("s_waitcnt lgkmcnt(0)" : __VA_ARGS__::"memory");                                 \
-    } while (0)
-    if (NA_ == 4 && NB_ == 4)
-        GEMM_F64_SETTLE("+v"(fa[0]), "+v"(fa[1]), "+v"(fa[NA_ - 2]), "+v"(fa[NA_ - 1]), "+v"(fb[0]), "+v"(fb[1]),
-                        "+v"(fb[NB_ - 2]), "+v"(fb[NB_ - 1]));
-    else if (NA_ == 4)
-        GEMM_F64_SETTLE("+v"(fa[0]), "+v"(fa[1]), "+v"(fa[NA_ - 2]), "+v"(fa[NA_ - 1]), "+v"(fb[0]), "+v"(fb[1]));
-    else if (NB_ == 4)
-        GEMM_F64_SETTLE("+v"(fa[0]), "+v"(fa[1]), "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[NB_ - 2]), "+v"(fb[NB_ - 1]));
-    else
-        GEMM_F64_SETTLE("+v"(fa[0]), "+v"(fa[1]), "+v"(fb[0]), "+v"(fb[1]));
-#undef GEMM_F64_SETTLE
-    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(voff), "s"(sbase), "s"(lds_addr)
+                 : "memory");
 }
 
 // One workgroup = 256 threads = 4 waves arranged WM x WN; each wave owns a (BM/WM) x (BN/WN)
@@ -169,34 +153,41 @@ gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t 
     // A chunk c = (iblk, h): lane l fetches the pair (row iblk*16 + l%16, k pair 4h + l/16).
     // B load r: BN = 128: row r, lane l fetches columns 2l, 2l+1;
     //           BN = 64 : rows 2r and 2r+1, lane l fetches row 2r + l/32, columns 2(l%32), +1.
-    const double *b_src = (BN == 128) ? B + (int64_t)(n0 + 2 * l)
-                                      : B + (int64_t)(l >> 5) * ldb + (n0 + 2 * (l & 31));
-    auto fetch_async_a = [&](int kt, int buf) {
-        char *stage = lds + buf * STAGE;
-        const int k0 = kt * BK;
+    // Every address is a wave-uniform 64-bit base, advanced with scalar arithmetic, plus a 32-bit
+    // per-lane byte offset computed once: FP64 MFMAs and ordinary vector ALU instructions compete
+    // for the same issue cycles on this chip, so the K loop should contain none of the latter.
+    // (The host only selects this path when BM * lda * 8 and 2 * ldb * 8 fit in 31 bits.)
+    constexpr int A_PER_WAVE = A_CHUNKS / 4, B_PER_WAVE = B_LOADS / 4;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
+    uint32_t a_voff[A_PER_WAVE];
 #pragma unroll
-        for (int q = 0; q < A_CHUNKS / 4; ++q) {
-            const int c = w + 4 * q;
-            const int iblk = c >> 1, h = c & 1;
-            int row = m0 + iblk * 16 + li;
-            if (GENERIC) row = row < M ? row : M - 1;
-            __builtin_amdgcn_global_load_lds((global_cptr)(A + (int64_t)row * lda + (k0 + 8 * h + 2 * lg)),
-                                             (lds_ptr)(stage + c * 1024), 16, 0, 0);
-        }
+    for (int q = 0; q < A_PER_WAVE; ++q) {
+        const int c = w + 4 * q;
+        const int iblk = c >> 1, h = c & 1;
+        int row = iblk * 16 + li;
+        if (GENERIC) row = (m0 + row < M) ? row : (M - 1 - m0);
+        a_voff[q] = (uint32_t)(((int64_t)row * lda + 8 * h + 2 * lg) * 8);
+    }
+    const uint32_t b_voff =
+        (BN == 128) ? (uint32_t)(16 * l) : (uint32_t)((((int64_t)(l >> 5)) * ldb + 2 * (l & 31)) * 8);
+    const char *const a_base = reinterpret_cast<const char *>(A + (int64_t)m0 * lda);
+    const char *const b_base = reinterpret_cast<const char *>(B + n0);
+    auto fetch_async_a = [&](int kt, int buf) {
+        const uint32_t dst = lds_base + buf * STAGE + w * 1024;
+        const char *src = a_base + (int64_t)kt * (BK * 8);
+#pragma unroll
+        for (int q = 0; q < A_PER_WAVE; ++q) async_copy16(a_voff[q], src, dst + q * 4096);
     };
     auto fetch_async_b = [&](int kt, int buf) {
-        char *stage = lds + buf * STAGE;
-        const int k0 = kt * BK;
+        // r = w + 4q: destination (r / 2) * B_PAIR + (r % 2) * B_ROW for BN = 128, r * B_PAIR for BN = 64
+        const uint32_t dst = lds_base + buf * STAGE + A_STAGE +
+                             ((BN == 128) ? (w >> 1) * B_PAIR + (w & 1) * B_ROW : w * B_PAIR);
+        const int64_t row_bytes = ldb * 8;
+        const char *src = b_base + (int64_t)(kt * BK + (BN == 128 ? w : 2 * w)) * row_bytes;
 #pragma unroll
-        for (int q = 0; q < B_LOADS / 4; ++q) {
-            const int r = w + 4 * q;
-            if (BN == 128)
-                __builtin_amdgcn_global_load_lds((global_cptr)(b_src + (int64_t)(k0 + r) * ldb),
-                                                 (lds_ptr)(stage + A_STAGE + (r >> 1) * B_PAIR + (r & 1) * B_ROW), 16, 0, 0);
-            else
-                __builtin_amdgcn_global_load_lds((global_cptr)(b_src + (int64_t)(k0 + 2 * r) * ldb),
-                                                 (lds_ptr)(stage + A_STAGE + r * B_PAIR), 16, 0, 0);
-        }
+        for (int q = 0; q < B_PER_WAVE; ++q)
+            async_copy16(b_voff, src + (int64_t)(BN == 128 ? 4 * q : 8 * q) * row_bytes,
+                         dst + q * ((BN == 128) ? 2 * B_PAIR : 4 * B_PAIR));
     };
 
     // ---- VGPR path (right-edge tiles, ragged K, unaligned operands): element-wise loads, zero
@@ -276,18 +267,17 @@ gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t 
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = v4d{0.0, 0.0, 0.0, 0.0};
 
-    auto mfma_half = [&](const v2d (&fa)[MI], const v2d (&fb)[NI]) {
+    // MFMAs lo .. hi-1 of the 2 * MI * NI that consume one half-stage, in the order e, mi, ni
+    auto mfma_range = [&](const v2d (&fa)[MI], const v2d (&fb)[NI], int lo, int hi) {
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-                acc[mi][ni] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[mi].x, fb[ni].x, acc[mi][ni], 0, 0, 0);
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-                acc[mi][ni] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[mi].y, fb[ni].y, acc[mi][ni], 0, 0, 0);
+        for (int idx = 0; idx < 2 * MI * NI; ++idx) {
+            if (idx < lo || idx >= hi) continue;
+            const int e = idx / (MI * NI), mi = (idx / NI) % MI, ni = idx % NI;
+            acc[mi][ni] = __builtin_amdgcn_mfma_f64_16x16x4f64(e ? fa[mi].y : fa[mi].x, e ? fb[ni].y : fb[ni].x,
+                                                               acc[mi][ni], 0, 0, 0);
+        }
     };
+    constexpr int HALF = 2 * MI * NI;
 
     v2d fa0[MI], fb0[NI], fa1[MI], fb1[NI];
 
@@ -298,27 +288,37 @@ gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t 
     }
     stage_barrier();
     read_frags(0, 0, fa0, fb0);
-    settle<false>(fa0, fb0);
 
     // Stage s lives in buffer s % 2.  Per iteration: the second half's fragments are read while the
     // first half's MFMAs run; then one barrier, after which buffer s % 2 is free for stage s + 2 and
     // stage s + 1 (fetched one iteration ago) is complete, so its first fragments are read and the
-    // next fetch is issued underneath the second half's MFMAs.
-    for (int s = 0; s < nk; ++s) {
-        const int cur = s & 1;
+    // next fetch is issued underneath the second half's MFMAs.  The loop is unrolled by two so that
+    // the buffer index is a compile-time constant and every LDS address is base register + immediate.
+    auto iteration = [&](int s, auto cur_tag) {
+        constexpr int cur = decltype(cur_tag)::value;
+        // The first MFMAs wait for fragments that were requested long ago; only then are the next
+        // reads queued, so that wait never covers a read that has just been issued.
+        mfma_range(fa0, fb0, 0, NI);
+        __builtin_amdgcn_sched_barrier(0);
         read_frags(cur, 1, fa1, fb1);
-        __builtin_amdgcn_sched_barrier(0);  // issue the reads first, then the MFMAs that hide them
-        mfma_half(fa0, fb0);
-        if (s >= 1 && s + 1 < nk) fetch_late(s + 1, cur ^ 1);
-        settle<true>(fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_range(fa0, fb0, NI, HALF);
+        if (GENERIC && s >= 1 && s + 1 < nk) fetch_late(s + 1, cur ^ 1);
+        stage_barrier();
         // unconditional (in the last iteration it re-reads a stale buffer and the values are never
-        // used): a fixed number of LDS reads in flight lets the compiler wait for exactly the older
-        // ones before the MFMAs below instead of draining the queue
+        // used): the number of LDS reads in flight is then the same on every path, and the compiler
+        // waits for exactly the older ones before the MFMAs below instead of draining the queue
         read_frags(cur ^ 1, 0, fa0, fb0);
         if (s + 2 < nk) fetch_early(s + 2, cur);
-        mfma_half(fa1, fb1);
-        settle<false>(fa0, fb0);  // the reads issued 32 MFMAs ago have long landed
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_range(fa1, fb1, 0, HALF);
+    };
+    int s = 0;
+    for (; s + 1 < nk; s += 2) {
+        iteration(s, std::integral_constant<int, 0>{});
+        iteration(s + 1, std::integral_constant<int, 1>{});
     }
+    if (s < nk) iteration(s, std::integral_constant<int, 0>{});
 
     // C is read and written exactly once per element, after the K loop.
     const int row_base = m0 + wm * TM + lg;
