@@ -25,7 +25,10 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), scaled
 # by the copy-kernel calibration; None until measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/mfma_128x128x16_c3_8192_pmc.txt: FETCH_SIZE 6 688 540 KiB x 2.0 + WRITE_SIZE 524 288 KiB x 1.0
+    ("c3_8192", "mfma_128x128x16"): (6688540 * 2.0 + 524288 * 1.0) * 1024,
+}
 
 
 def log(*a):
