@@ -85,6 +85,15 @@ __device__ __forceinline__ void async_copy16(uint32_t voff, const void *sbase, u
                  : "memory");
 }
 
+// The 4-byte form: lane l copies the 4 bytes at sbase + voff(l) to LDS address lds_addr + 4 * l.
+__device__ __forceinline__ void async_copy4(uint32_t voff, const void *sbase, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :
+                 : "v"(voff), "s"(sbase), "s"(lds_addr)
+                 : "memory");
+}
+
 // One workgroup = 256 threads = 4 waves arranged WM x WN; each wave owns a (BM/WM) x (BN/WN)
 // patch of the macro-tile as MI x NI accumulator tiles of 16 x 16.
 //
@@ -143,11 +152,14 @@ gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t 
     // Number of leading stages fetched by the asynchronous global->LDS path, per operand.  Rows of
     // an A tile that lie below the matrix are redirected to row M - 1: they only feed rows of C
     // that are never stored, so no zero fill is needed in M and such tiles stay on the fast path.
-    // Columns of B to the right of the matrix cannot be redirected pairwise (N may be odd), so
-    // tiles on the right edge stage B through VGPRs.  The ragged last K stage always does, for
-    // both operands, because there zeros are required.
+    // Columns of B to the right of the matrix feed only columns of C that are never stored either;
+    // there the lanes whose pair of columns lies outside are switched off (their LDS cells keep
+    // stale bits) and, when N is odd, the last column is fetched on its own, four bytes per lane.
+    // Only the ragged last K stage goes through VGPRs, for both operands, because there zeros are
+    // required: k >= K contributes to every output.
     const int nk_async_a = GENERIC ? (vec_ok ? K / BK : 0) : nk;
-    const int nk_async_b = GENERIC ? ((vec_ok && n0 + BN <= N) ? K / BK : 0) : nk;
+    const int nk_async_b = nk_async_a;
+    const bool b_edge = GENERIC && (n0 + BN > N);
 
     // ---- asynchronous path: each wave issues its share of 1 KiB global->LDS loads -------------
     // A chunk c = (iblk, h): lane l fetches the pair (row iblk*16 + l%16, k pair 4h + l/16).
@@ -184,10 +196,26 @@ gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t 
                              ((BN == 128) ? (w >> 1) * B_PAIR + (w & 1) * B_ROW : w * B_PAIR);
         const int64_t row_bytes = ldb * 8;
         const char *src = b_base + (int64_t)(kt * BK + (BN == 128 ? w : 2 * w)) * row_bytes;
+        if (!b_edge) {
 #pragma unroll
-        for (int q = 0; q < B_PER_WAVE; ++q)
-            async_copy16(b_voff, src + (int64_t)(BN == 128 ? 4 * q : 8 * q) * row_bytes,
-                         dst + q * ((BN == 128) ? 2 * B_PAIR : 4 * B_PAIR));
+            for (int q = 0; q < B_PER_WAVE; ++q)
+                async_copy16(b_voff, src + (int64_t)(BN == 128 ? 4 * q : 8 * q) * row_bytes,
+                             dst + q * ((BN == 128) ? 2 * B_PAIR : 4 * B_PAIR));
+        } else {
+            const int valid = N - n0;                     // 1 .. BN-1 columns of this tile exist
+            const bool pair_ok = 2 * (l % JP) + 1 < valid;
+            const int jt = valid - 1;                     // last column; fetched alone when valid is odd
+#pragma unroll
+            for (int q = 0; q < B_PER_WAVE; ++q) {
+                const char *rsrc = src + (int64_t)(BN == 128 ? 4 * q : 8 * q) * row_bytes;
+                const uint32_t rdst = dst + q * ((BN == 128) ? 2 * B_PAIR : 4 * B_PAIR);
+                if (pair_ok) async_copy16(b_voff, rsrc, rdst);
+                if ((valid & 1) && l < 2) {
+                    async_copy4(4 * l, rsrc + jt * 8, rdst + jt * 8);
+                    if (BN == 64) async_copy4(4 * l, rsrc + row_bytes + jt * 8, rdst + B_ROW + jt * 8);
+                }
+            }
+        }
     };
 
     // ---- VGPR path (right-edge tiles, ragged K, unaligned operands): element-wise loads, zero
@@ -320,28 +348,35 @@ gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t 
     }
     if (s < nk) iteration(s, std::integral_constant<int, 0>{});
 
-    // C is read and written exactly once per element, after the K loop.
+    // C is read and written exactly once per element, after the K loop.  Loads are issued in batches
+    // of two 16-row blocks (up to 32 per lane in flight) before the first is consumed: the epilogue
+    // is latency-bound, so its duration is the number of batches times the memory latency.
     const int row_base = m0 + wm * TM + lg;
     const int col_base = n0 + wn * TN + li;
+    constexpr int MB = (MI >= 2) ? 2 : 1;
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-        double cin[NI][4];
+    for (int mb = 0; mb < MI; mb += MB) {
+        double cin[MB][NI][4];
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+        for (int mi = mb; mi < mb + MB; ++mi)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = row_base + mi * 16 + 4 * r, col = col_base + ni * 16;
-                if (!GENERIC || tile_full || (row < M && col < N)) cin[ni][r] = C[(int64_t)row * ldc + col];
-                else cin[ni][r] = 0.0;
-            }
+            for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+                for (int r = 0; r < 4; ++r) {
+                    const int row = row_base + mi * 16 + 4 * r, col = col_base + ni * 16;
+                    if (!GENERIC || tile_full || (row < M && col < N)) cin[mi - mb][ni][r] = C[(int64_t)row * ldc + col];
+                    else cin[mi - mb][ni][r] = 0.0;
+                }
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = row_base + mi * 16 + 4 * r, col = col_base + ni * 16;
-                if (!GENERIC || tile_full || (row < M && col < N))
-                    C[(int64_t)row * ldc + col] = cin[ni][r] + acc[mi][ni][r];
-            }
+        for (int mi = mb; mi < mb + MB; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = row_base + mi * 16 + 4 * r, col = col_base + ni * 16;
+                    if (!GENERIC || tile_full || (row < M && col < N))
+                        C[(int64_t)row * ldc + col] = cin[mi - mb][ni][r] + acc[mi][ni][r];
+                }
     }
 }
 

@@ -96,9 +96,11 @@ def test_tile_mapping_keeps_an_xcd_compact():
 
 def test_variant_selection_follows_tile_quantisation():
     name = lambda M, N, K: binding.gemm_f64_variant_name(binding.gemm_f64_choose_variant(M, N, K, 256))
-    assert name(8192, 8192, 8192) == "mfma_128x128x16"
+    assert name(8192, 8192, 8192) == "mfma_64x128x16"
     # 2088 x 2049 needs 289 tiles of 128x128, two rounds on 256 compute units at ~56 % use: a smaller tile wins
-    assert name(2088, 2049, 2047) != "mfma_128x128x16"
+    assert name(2088, 2049, 2047) == "mfma_64x64x16"
+    # 2048^2 as 256 tiles of 128x128 leaves every compute unit with a single workgroup
+    assert name(2048, 2048, 2048) != "mfma_128x128x16"
     for (M, N, K) in [(1, 1, 1), (256, 256, 256), (2048, 2048, 2048), (16384, 16384, 256), (100000, 3, 7)]:
         v = binding.gemm_f64_choose_variant(M, N, K, 256)
         assert 1 <= v < binding.gemm_f64_variant_count()
