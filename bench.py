@@ -28,6 +28,8 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {
     # profiles/mfma_128x128x16_c3_8192_pmc.txt: FETCH_SIZE 6 688 540 KiB x 2.0 + WRITE_SIZE 524 288 KiB x 1.0
     ("c3_8192", "mfma_128x128x16"): (6688540 * 2.0 + 524288 * 1.0) * 1024,
+    # profiles/mfma_64x128x16_c3_8192_pmc.txt: FETCH_SIZE 8 739 400 KiB x 2.0 + WRITE_SIZE 524 288 KiB x 1.0
+    ("c3_8192", "mfma_64x128x16"): (8739400 * 2.0 + 524288 * 1.0) * 1024,
 }
 
 
@@ -78,8 +80,8 @@ def copy_calibration():
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c3_8192")
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--seed", type=int, default=0)

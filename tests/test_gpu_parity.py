@@ -62,6 +62,42 @@ def test_misaligned_base_pointers(gpu_device, variant):
         gpu_util.check_against_oracle(A, B, C, c2[:, :N], kind == "int", "misaligned %s" % kind)
 
 
+@pytest.mark.parametrize("variant", MFMA_VARIANTS)
+def test_right_and_bottom_edges_on_the_async_path(gpu_device, variant):
+    # aligned operands with even leading dimensions keep edge tiles on the global->LDS path: rows below
+    # the matrix are redirected, column pairs outside it are masked and an odd last column is copied
+    # on its own.  Every remainder class that matters is visited: 1, 2, odd, even, 15..17, one short.
+    K = 80
+    for (M, N) in [(130, 129), (129, 130), (67, 131), (200, 143), (75, 144), (190, 145), (64, 191), (127, 255),
+                   (128, 257), (65, 65), (1, 1), (16, 2), (33, 3)]:
+        lda, ldb, ldc = K + 2, N + (N % 2) + 4, N + 3
+        Ab, A = synth.matrix(11, synth.TAG_A, M, K, lda, "int")
+        Bb, B = synth.matrix(11, synth.TAG_B, K, N, ldb, "int")
+        Cb, C = synth.matrix(11, synth.TAG_C, M, N, ldc, "int")
+        a2, b2, c2 = gpu_util.run_device(Ab, Bb, Cb, M, N, K, variant=variant)
+        what = "variant %d edge %s" % (variant, (M, N, K))
+        assert synth.padding_intact(c2, N) and synth.padding_intact(a2, K) and synth.padding_intact(b2, N), what
+        gpu_util.check_against_oracle(A, B, C, c2[:, :N], True, what)
+
+
+def test_stale_lds_bits_do_not_reach_valid_columns(gpu_device):
+    # a run on NaN data leaves NaN bits in LDS; the next launch has masked column pairs whose LDS cells
+    # keep whatever was there, which must only ever feed columns that are not stored
+    M, N, K = 256, 256, 64
+    nan = torch.full((M, K), float("nan"), dtype=torch.float64, device="cuda:0")
+    out = torch.zeros((M, N), dtype=torch.float64, device="cuda:0")
+    for v in MFMA_VARIANTS:
+        binding.gemm_f64_ex(M, N, K, nan, K, nan[:K, :].contiguous().repeat(1, N // K), N, out, N, variant=v)
+    torch.cuda.synchronize()
+    M, N, K = 70, 67, 48
+    Ab, A = synth.matrix(12, synth.TAG_A, M, K, K, "int")
+    Bb, B = synth.matrix(12, synth.TAG_B, K, N, N + 1, "int")
+    Cb, C = synth.matrix(12, synth.TAG_C, M, N, N + 1, "int")
+    for v in MFMA_VARIANTS:
+        _, _, c2 = gpu_util.run_device(Ab, Bb, Cb, M, N, K, variant=v)
+        gpu_util.check_against_oracle(A, B, C, c2[:, :N], True, "after NaN run, variant %d" % v)
+
+
 ORDER_FREE_PINS = [pins.pin_all_ones_small, pins.pin_identity, pins.pin_column_sums, pins.pin_rank_one,
                    pins.pin_one_hot_index, pins.pin_tiny_exact, pins.pin_integer_exact,
                    pins.pin_error_bound, pins.pin_ld_independence, pins.pin_degenerate]
