@@ -43,11 +43,14 @@ hipError_t launch_mfma(int M, int N, int K, const double *A, int64_t lda, const 
     // The lean kernel assumes full tiles everywhere, whole K stages and 16-byte-aligned operands.
     const bool lean = vec && (M % BM == 0) && (N % BN == 0) && (K % kBK == 0);
     if (lean)
-        hipLaunchKernelGGL((gemm_f64_mfma_kernel<BM, BN, WM, WN, false>), grid, block, 0, stream, M, N, K, A, lda, B,
+        hipLaunchKernelGGL((gemm_f64_mfma_kernel<BM, BN, WM, WN, kLean>), grid, block, 0, stream, M, N, K, A, lda, B,
                            ldb, C, ldc, tiles_m, tiles_n, 1);
+    else if (vec)
+        hipLaunchKernelGGL((gemm_f64_mfma_kernel<BM, BN, WM, WN, kGeneric>), grid, block, 0, stream, M, N, K, A, lda,
+                           B, ldb, C, ldc, tiles_m, tiles_n, 1);
     else
-        hipLaunchKernelGGL((gemm_f64_mfma_kernel<BM, BN, WM, WN, true>), grid, block, 0, stream, M, N, K, A, lda, B,
-                           ldb, C, ldc, tiles_m, tiles_n, vec ? 1 : 0);
+        hipLaunchKernelGGL((gemm_f64_mfma_kernel<BM, BN, WM, WN, kStaged>), grid, block, 0, stream, M, N, K, A, lda,
+                           B, ldb, C, ldc, tiles_m, tiles_n, 0);
     return hipGetLastError();
 }
 

@@ -34,6 +34,7 @@ constexpr int kXcds = 8;    // workgroups are dealt round-robin to 8 XCDs, each 
 constexpr int kGroupM = 8;  // tile rows per group of the grouped tile order
 constexpr int kBK = 16;     // depth of one LDS stage
 constexpr int kThreads = 256;
+constexpr int kLean = 0, kGeneric = 1, kStaged = 2;  // kernel modes, see gemm_f64_mfma_kernel
 
 // Workgroup id -> tile coordinates.  Block b runs on XCD b % kXcds.  Each XCD receives a
 // contiguous run of the "grouped" tile order (kGroupM tile rows at a time, column by column
@@ -109,16 +110,23 @@ __device__ __forceinline__ void async_copy4(uint32_t voff, const void *sbase, ui
 // Both layouts are exactly what a 16-byte-per-lane global->LDS load writes (lane-linear 1 KiB), so
 // full tiles are staged with global_load_lds_dwordx4 and never pass through VGPRs.
 //
-// GENERIC = false: every tile is full, K is a multiple of 16, A and B are 16-byte aligned with
-// even leading dimensions (checked on the host).  GENERIC = true adds the element-wise, zero-filled
-// path through VGPRs for edge tiles, the ragged last K stage and unaligned operands (vec_ok = 0).
-template <int BM, int BN, int WM, int WN, bool GENERIC>
+// MODE = kLean: every tile is full, K is a multiple of 16, A and B are 16-byte aligned with even
+// leading dimensions (checked on the host); only the asynchronous path is compiled in.
+// MODE = kGeneric adds the element-wise, zero-filled path through VGPRs for the ragged last K stage
+// (synchronous: once per tile) and handles edge tiles; it also runs unaligned operands (vec_ok = 0)
+// through that synchronous path, slowly.
+// MODE = kStaged is for unaligned operands: every stage goes through VGPRs, loaded two stages ahead
+// and written to LDS one stage ahead, at the price of 16 to 32 more live registers.
+template <int BM, int BN, int WM, int WN, int MODE>
 __global__ void __launch_bounds__(kThreads, 2)
 gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t lda,
                      const double *__restrict__ B, int64_t ldb, double *__restrict__ C, int64_t ldc,
                      int tiles_m, int tiles_n, int vec_ok)
 {
     constexpr int BK = kBK;
+    constexpr bool GENERIC = MODE != kLean;
+    constexpr bool STAGED = MODE == kStaged;
+    static_assert(MODE == kLean || MODE == kGeneric || MODE == kStaged, "kernel mode");
     static_assert(WM * WN == 4, "four waves per workgroup");
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int MI = TM / 16, NI = TN / 16;
@@ -157,7 +165,7 @@ gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t 
     // stale bits) and, when N is odd, the last column is fetched on its own, four bytes per lane.
     // Only the ragged last K stage goes through VGPRs, for both operands, because there zeros are
     // required: k >= K contributes to every output.
-    const int nk_async_a = GENERIC ? (vec_ok ? K / BK : 0) : nk;
+    const int nk_async_a = STAGED ? 0 : GENERIC ? (vec_ok ? K / BK : 0) : nk;
     const int nk_async_b = nk_async_a;
     const bool b_edge = GENERIC && (n0 + BN > N);
 
@@ -221,10 +229,8 @@ gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t 
     // ---- VGPR path (right-edge tiles, ragged K, unaligned operands): element-wise loads, zero
     // outside the logical matrices, written to LDS in the same layout.  Both operands are zeroed
     // for k >= K, so padding only ever forms 0 * 0.  Synchronous: used where it is rare.
-    auto fetch_sync_a = [&](int kt, int buf) {
-        char *stage = lds + buf * STAGE;
+    auto load_regs_a = [&](int kt, double (&ra)[2 * NA]) {
         const int k0 = kt * BK;
-        double ra[2 * NA];
 #pragma unroll
         for (int q = 0; q < NA; ++q) {
             const int row = m0 + li + 16 * w + 64 * (q >> 1), k = k0 + 2 * (lg + 4 * (q & 1));
@@ -232,6 +238,9 @@ gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t 
             ra[2 * q] = (row < M && k < K) ? p[0] : 0.0;
             ra[2 * q + 1] = (row < M && k + 1 < K) ? p[1] : 0.0;
         }
+    };
+    auto store_regs_a = [&](int buf, const double (&ra)[2 * NA]) {
+        char *stage = lds + buf * STAGE;
 #pragma unroll
         for (int q = 0; q < NA; ++q) {
             const int i = li + 16 * w + 64 * (q >> 1), kp = lg + 4 * (q & 1);
@@ -241,10 +250,8 @@ gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t 
             *reinterpret_cast<v2d *>(stage + (((i >> 4) << 1) | (kp >> 2)) * 1024 + (kp & 3) * 256 + (i & 15) * 16) = v;
         }
     };
-    auto fetch_sync_b = [&](int kt, int buf) {
-        char *stage = lds + buf * STAGE;
+    auto load_regs_b = [&](int kt, double (&rb)[2 * NB]) {
         const int k0 = kt * BK;
-        double rb[2 * NB];
 #pragma unroll
         for (int q = 0; q < NB; ++q) {
             const int kk = k0 + l / JP + (64 / JP) * w + (kThreads / JP) * q, col = n0 + 2 * (l % JP);
@@ -252,6 +259,9 @@ gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t 
             rb[2 * q] = (kk < K && col < N) ? p[0] : 0.0;
             rb[2 * q + 1] = (kk < K && col + 1 < N) ? p[1] : 0.0;
         }
+    };
+    auto store_regs_b = [&](int buf, const double (&rb)[2 * NB]) {
+        char *stage = lds + buf * STAGE;
 #pragma unroll
         for (int q = 0; q < NB; ++q) {
             const int kk = l / JP + (64 / JP) * w + (kThreads / JP) * q, j = 2 * (l % JP);
@@ -261,6 +271,19 @@ gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t 
             *reinterpret_cast<v2d *>(stage + A_STAGE + (kk >> 1) * B_PAIR + (kk & 1) * B_ROW + j * 8) = v;
         }
     };
+    auto fetch_sync_a = [&](int kt, int buf) {
+        double ra[2 * NA];
+        load_regs_a(kt, ra);
+        store_regs_a(buf, ra);
+    };
+    auto fetch_sync_b = [&](int kt, int buf) {
+        double rb[2 * NB];
+        load_regs_b(kt, rb);
+        store_regs_b(buf, rb);
+    };
+    // kStaged: the registers that carry a stage from its loads (after one barrier) to its LDS
+    // writes (before the next)
+    double sa[STAGED ? 2 * NA : 1], sb[STAGED ? 2 * NB : 1];
     // issue what can be fetched asynchronously for stage kt (as early as its buffer is free) ...
     auto fetch_early = [&](int kt, int buf) {
         if (kt < nk_async_a) fetch_async_a(kt, buf);
@@ -272,6 +295,8 @@ gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t 
         if (kt >= nk_async_a) fetch_sync_a(kt, buf);
         if (kt >= nk_async_b) fetch_sync_b(kt, buf);
     };
+    (void)sa;
+    (void)sb;
 
     // ---- operand fragments: one half-stage (h) = two MFMA k-steps ------------------------------
     const int a_frag = ((wm * (TM / 16)) << 1) * 1024 + l * 16;              // + mi*2048 + h*1024
@@ -331,13 +356,27 @@ gemm_f64_mfma_kernel(int M, int N, int K, const double *__restrict__ A, int64_t 
         read_frags(cur, 1, fa1, fb1);
         __builtin_amdgcn_sched_barrier(0);
         mfma_range(fa0, fb0, NI, HALF);
-        if (GENERIC && s >= 1 && s + 1 < nk) fetch_late(s + 1, cur ^ 1);
+        if constexpr (STAGED) {
+            if (s >= 1 && s + 1 < nk) {  // stage s + 1 was loaded during the previous iteration
+                store_regs_a(cur ^ 1, reinterpret_cast<const double(&)[2 * NA]>(sa));
+                store_regs_b(cur ^ 1, reinterpret_cast<const double(&)[2 * NB]>(sb));
+            }
+        } else if (GENERIC && s >= 1 && s + 1 < nk) {
+            fetch_late(s + 1, cur ^ 1);
+        }
         stage_barrier();
         // unconditional (in the last iteration it re-reads a stale buffer and the values are never
         // used): the number of LDS reads in flight is then the same on every path, and the compiler
         // waits for exactly the older ones before the MFMAs below instead of draining the queue
         read_frags(cur ^ 1, 0, fa0, fb0);
-        if (s + 2 < nk) fetch_early(s + 2, cur);
+        if constexpr (STAGED) {
+            if (s + 2 < nk) {
+                load_regs_a(s + 2, reinterpret_cast<double(&)[2 * NA]>(sa));
+                load_regs_b(s + 2, reinterpret_cast<double(&)[2 * NB]>(sb));
+            }
+        } else if (s + 2 < nk) {
+            fetch_early(s + 2, cur);
+        }
         __builtin_amdgcn_sched_barrier(0);
         mfma_range(fa1, fb1, 0, HALF);
     };
