@@ -1,4 +1,4 @@
-"""Compile the CPU oracle (plain C, gcc) into oracle/liboracle_f64.so.
+"""Compile the CPU oracles (plain C, gcc) into oracle/liboracle_gemm.so.
 
 Test infrastructure only.  The flags matter for what the oracle means:
 -ffp-contract=off keeps the product and the sum as two separately rounded
@@ -10,18 +10,18 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "gemm_ref.c")
-LIB = os.path.join(HERE, "liboracle_f64.so")
+SOURCES = [os.path.join(HERE, "gemm_ref.c"), os.path.join(HERE, "gemm_ref_f32.c")]
+LIB = os.path.join(HERE, "liboracle_gemm.so")
 
 FLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
          "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra"]
 
 
 def build(force: bool = True) -> str:
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(os.path.getmtime(p) for p in SOURCES):
         return LIB
     tmp = LIB + ".tmp.%d" % os.getpid()
-    subprocess.check_call(["gcc", *FLAGS, SRC, "-o", tmp, "-lm"])
+    subprocess.check_call(["gcc", *FLAGS, *SOURCES, "-o", tmp, "-lm"])
     os.replace(tmp, LIB)
     return LIB
 

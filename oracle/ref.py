@@ -26,6 +26,10 @@ def _load():
             fn = getattr(lib, name)
             fn.argtypes = [i64, i64, i64, dp, i64, dp, i64, dp, i64]
             fn.restype = ctypes.c_int
+        for name in ("gemm_f32_ref", "gemm_f32_ref_ijk", "gemm_f32_absref"):
+            fn = getattr(lib, name)
+            fn.argtypes = [i64, i64, i64, dp, i64, dp, i64, dp, i64]
+            fn.restype = ctypes.c_int
         lib.gemm_f64_ref_threads.restype = ctypes.c_int
         lib.gemm_f64_ref_set_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -33,19 +37,23 @@ def _load():
 
 
 def _ld(x: np.ndarray) -> int:
-    assert x.dtype == np.float64 and x.ndim == 2
+    assert x.dtype in (np.float64, np.float32) and x.ndim == 2
+    sz = x.dtype.itemsize
     if x.size == 0:
         # no element is touched; any legal leading dimension will do
-        return max(1, x.shape[1], x.strides[0] // 8 if x.strides[0] % 8 == 0 else 1)
+        return max(1, x.shape[1], x.strides[0] // sz if x.strides[0] % sz == 0 else 1)
     if x.shape[1] > 1:
-        assert x.strides[1] == 8, "last axis must be contiguous"
+        assert x.strides[1] == sz, "last axis must be contiguous"
     if x.shape[0] > 1:
-        assert x.strides[0] % 8 == 0 and x.strides[0] > 0
-        return x.strides[0] // 8
+        assert x.strides[0] % sz == 0 and x.strides[0] > 0
+        return x.strides[0] // sz
     return max(1, x.shape[1])
 
 
 def _call(name, A, B, C, lda=None, ldb=None, ldc=None):
+    want = np.float32 if "f32" in name else np.float64
+    assert A.dtype == want and B.dtype == want, "%s takes %s operands" % (name, np.dtype(want).name)
+    assert C.dtype == (np.float64 if name.endswith("absref") else want)
     M, K = A.shape
     K2, N = B.shape
     assert K2 == K and C.shape == (M, N)
@@ -73,6 +81,20 @@ def gemm_f64_absref(A, B, C):
     return _call("gemm_f64_absref", A, B, C)
 
 
+def gemm_f32_ref(A, B, C):
+    """float32 C += A @ B, every product and sum rounded to binary32 (Section 2.13), in place."""
+    return _call("gemm_f32_ref", A, B, C)
+
+
+def gemm_f32_ref_ijk(A, B, C):
+    return _call("gemm_f32_ref_ijk", A, B, C)
+
+
+def gemm_f32_absref(A, B, S):
+    """float64 S += |A| @ |B| for float32 operands: the tolerance scale."""
+    return _call("gemm_f32_absref", A, B, S)
+
+
 def raw(name):
     """The raw C entry point (for argument-validation tests)."""
     return getattr(_load(), name)
@@ -86,6 +108,10 @@ def set_ref_threads(n: int) -> None:
     _load().gemm_f64_ref_set_threads(int(n))
 
 
+def _ref_fn(A):
+    return gemm_f32_ref if A.dtype == np.float32 else gemm_f64_ref
+
+
 def ref_rows(A, B, C0, rows):
     """Oracle result for selected rows only: out[r] = C0[rows[r]] + A[rows[r]] @ B.
 
@@ -96,7 +122,7 @@ def ref_rows(A, B, C0, rows):
     rows = np.asarray(rows, dtype=np.int64)
     Ar = np.ascontiguousarray(A[rows, :])
     Cr = np.ascontiguousarray(C0[rows, :])
-    return gemm_f64_ref(Ar, B, Cr)
+    return _ref_fn(A)(Ar, B, Cr)
 
 
 def abs_rows(A, B, rows):
@@ -104,4 +130,4 @@ def abs_rows(A, B, rows):
     rows = np.asarray(rows, dtype=np.int64)
     Ar = np.ascontiguousarray(A[rows, :])
     S = np.zeros((len(rows), B.shape[1]), dtype=np.float64)
-    return gemm_f64_absref(Ar, B, S)
+    return (gemm_f32_absref if A.dtype == np.float32 else gemm_f64_absref)(Ar, B, S)

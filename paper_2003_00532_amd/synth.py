@@ -28,6 +28,7 @@ TAG_A, TAG_B, TAG_C = 1, 2, 3
 # arithmetic produces, so both "padding was read" (NaN leaks into C) and
 # "padding was written" (pattern changed) are detectable.
 PAD_BITS = 0x7FF8_5EED_0BAD_F00D
+PAD_BITS32 = 0x7FC5_EED5  # the same idea for float32 buffers
 
 
 def _mix_scalar(z: int) -> int:
@@ -71,6 +72,11 @@ def values_int(h: np.ndarray) -> np.ndarray:
     return ((h >> np.uint64(11)) % np.uint64(9)).astype(np.float64) - 4.0
 
 
+def values_uniform32(h: np.ndarray) -> np.ndarray:
+    """Top 24 bits -> multiples of 2^-23 in [-1, 1), exactly representable in float32."""
+    return ((h >> np.uint64(40)).astype(np.float64) * (2.0 ** -23) - 1.0).astype(np.float32)
+
+
 _KINDS = ("uniform", "int", "ones", "zeros")
 
 
@@ -85,7 +91,10 @@ def fill(out: np.ndarray, seed: int, tag: int, kind: str, row0: int = 0,
     if kind == "zeros":
         out[...] = 0.0
         return out
-    conv = values_uniform if kind == "uniform" else values_int
+    if out.dtype == np.float32:
+        conv = values_uniform32 if kind == "uniform" else (lambda h: values_int(h).astype(np.float32))
+    else:
+        conv = values_uniform if kind == "uniform" else values_int
     cidx = np.arange(cols, dtype=np.uint64)
     for r in range(0, rows, chunk_rows):
         n = min(chunk_rows, rows - r)
@@ -94,28 +103,35 @@ def fill(out: np.ndarray, seed: int, tag: int, kind: str, row0: int = 0,
     return out
 
 
-def padded(rows: int, cols: int, ld: int, pinned: bool = False) -> np.ndarray:
-    """A (rows, ld) float64 buffer whose every element is the padding sentinel.
+def _bits_view(buf: np.ndarray):
+    return (buf.view(np.uint32), np.uint32(PAD_BITS32)) if buf.dtype == np.float32 else (buf.view(np.uint64), np.uint64(PAD_BITS))
+
+
+def padded(rows: int, cols: int, ld: int, pinned: bool = False, dtype=np.float64) -> np.ndarray:
+    """A (rows, ld) buffer of `dtype` (float64 or float32) whose every element is the padding sentinel.
 
     With pinned=True the storage is page-locked host memory obtained from torch
     (a fresh allocation, never a registration of existing memory).
     """
     assert ld >= max(1, cols)
+    dtype = np.dtype(dtype)
     if pinned:
         import torch
-        t = torch.empty((max(rows, 1), ld), dtype=torch.float64, pin_memory=True)
+        tdt = torch.float32 if dtype == np.float32 else torch.float64
+        t = torch.empty((max(rows, 1), ld), dtype=tdt, pin_memory=True)
         buf = t.numpy()[:rows]
     else:
-        buf = np.empty((rows, ld), dtype=np.float64)
-    buf.view(np.uint64)[...] = np.uint64(PAD_BITS)
+        buf = np.empty((rows, ld), dtype=dtype)
+    view, pad = _bits_view(buf)
+    view[...] = pad
     return buf
 
 
 def matrix(seed: int, tag: int, rows: int, cols: int, ld: int = None,
-           kind: str = "uniform"):
+           kind: str = "uniform", dtype=np.float64):
     """Return (buffer, view): buffer is (rows, ld) with sentinel padding, view = buffer[:, :cols]."""
     ld = max(1, cols) if ld is None else ld
-    buf = padded(rows, cols, ld)
+    buf = padded(rows, cols, ld, dtype=dtype)
     view = buf[:, :cols]
     fill(view, seed, tag, kind)
     return buf, view
@@ -125,7 +141,8 @@ def padding_intact(buf: np.ndarray, cols: int) -> bool:
     """True when every element at column >= cols still holds the sentinel bits."""
     if buf.shape[1] == cols:
         return True
-    return bool(np.all(buf.view(np.uint64)[:, cols:] == np.uint64(PAD_BITS)))
+    view, pad = _bits_view(buf)
+    return bool(np.all(view[:, cols:] == pad))
 
 
 @dataclass(frozen=True)
@@ -159,13 +176,13 @@ WORKLOADS = {
 }
 
 
-def workload_inputs(w: Workload, seed: int = 0, integer: bool = False):
+def workload_inputs(w: Workload, seed: int = 0, integer: bool = False, dtype=np.float64):
     """(Abuf, Bbuf, Cbuf) padded host buffers for a workload; logical parts are [:, :K] etc."""
     kind = "int" if integer else "uniform"
     ckind = kind if w.c_kind == "uniform" else w.c_kind
-    Abuf, _ = matrix(seed, TAG_A, w.M, w.K, w.lda, kind)
-    Bbuf, _ = matrix(seed, TAG_B, w.K, w.N, w.ldb, kind)
-    Cbuf, _ = matrix(seed, TAG_C, w.M, w.N, w.ldc, ckind)
+    Abuf, _ = matrix(seed, TAG_A, w.M, w.K, w.lda, kind, dtype)
+    Bbuf, _ = matrix(seed, TAG_B, w.K, w.N, w.ldb, kind, dtype)
+    Cbuf, _ = matrix(seed, TAG_C, w.M, w.N, w.ldc, ckind, dtype)
     return Abuf, Bbuf, Cbuf
 
 

@@ -8,6 +8,7 @@ CPU oracle (which they are meant to pin), to deliberately wrong variants (to
 show that a plausible mistake is caught) and, through a device adapter, the
 order-independent ones are reused on the HIP path.
 """
+import contextlib
 import os
 from fractions import Fraction
 
@@ -17,9 +18,59 @@ from paper_2003_00532_amd import synth
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
+# The element type the pins are stated for.  float64 is the path's own precision; the float32 variant
+# (the paper's Section 2.13 substitution) re-uses every pin with u = 2^-24 via `with precision(np.float32)`.
+DT = np.dtype(np.float64)
+
+
+@contextlib.contextmanager
+def precision(dtype):
+    global DT
+    old, DT = DT, np.dtype(dtype)
+    try:
+        yield
+    finally:
+        DT = old
+
+
+def mant_bits():
+    return 24 if DT == np.float32 else 53
+
 
 def bits(x):
-    return np.ascontiguousarray(x).view(np.uint64)
+    x = np.ascontiguousarray(x)
+    return x.view(np.uint32 if x.dtype == np.float32 else np.uint64)
+
+
+def rn(x: Fraction) -> float:
+    """Round an exact rational to the nearest DT value, ties to even (normal range only)."""
+    if x == 0:
+        return 0.0
+    p = mant_bits()
+    sign = -1 if x < 0 else 1
+    x = abs(x)
+    e = x.numerator.bit_length() - x.denominator.bit_length()
+    if Fraction(2) ** e > x:
+        e -= 1
+    assert Fraction(2) ** e <= x < Fraction(2) ** (e + 1)
+    scaled = x / Fraction(2) ** (e - p + 1)          # in [2^(p-1), 2^p)
+    q, r = divmod(scaled.numerator, scaled.denominator)
+    twice = 2 * r
+    if twice > scaled.denominator or (twice == scaled.denominator and (q & 1)):
+        q += 1
+    return float(sign * Fraction(q) * Fraction(2) ** (e - p + 1))
+
+
+def ones(shape, value=1.0):
+    return np.full(shape, value, dtype=DT)
+
+
+def zeros(shape):
+    return np.zeros(shape, dtype=DT)
+
+
+def eye(n):
+    return np.eye(n, dtype=DT)
 
 
 def assert_bitwise(got, want, what=""):
@@ -34,7 +85,11 @@ def assert_bitwise(got, want, what=""):
 
 
 def _mat(seed, tag, rows, cols, ld=None, kind="int"):
-    return synth.matrix(seed, tag, rows, cols, ld, kind)
+    return synth.matrix(seed, tag, rows, cols, ld, kind, DT)
+
+
+def _abs_product(A, B):
+    return np.abs(A.astype(np.float64)) @ np.abs(B.astype(np.float64))
 
 
 # ---------------------------------------------------------------- closed forms
@@ -50,16 +105,16 @@ def pin_paper_all_ones(impl, shapes=None):
     for M, N, K, cin, want in rows:
         if shapes is not None and (M, N, K) not in shapes:
             continue
-        A = np.ones((M, K)); B = np.ones((K, N)); C = np.full((M, N), cin)
+        A = ones((M, K)); B = ones((K, N)); C = ones((M, N), cin)
         impl(A, B, C)
-        assert_bitwise(C, np.full((M, N), want), "all-ones %dx%dx%d" % (M, N, K))
+        assert_bitwise(C, ones((M, N), want), "all-ones %dx%dx%d" % (M, N, K))
 
 
 def pin_all_ones_small(impl):
     for (M, N, K) in [(1, 1, 1), (3, 5, 7), (17, 33, 65), (64, 48, 200)]:
-        A = np.ones((M, K)); B = np.ones((K, N)); C = np.ones((M, N))
+        A = ones((M, K)); B = ones((K, N)); C = ones((M, N))
         impl(A, B, C)
-        assert_bitwise(C, np.full((M, N), 1.0 + K), "ones %s" % ((M, N, K),))
+        assert_bitwise(C, ones((M, N), 1.0 + K), "ones %s" % ((M, N, K),))
 
 
 def pin_identity(impl):
@@ -68,12 +123,12 @@ def pin_identity(impl):
     _, X = _mat(5, synth.TAG_B, n, 29, kind="uniform")
     _, C0 = _mat(5, synth.TAG_C, n, 29, kind="uniform")
     C = C0.copy()
-    impl(np.eye(n), X, C)
+    impl(eye(n), X, C)
     assert_bitwise(C, C0 + X, "A = I")
     _, Y = _mat(6, synth.TAG_A, 23, n, kind="uniform")
     _, D0 = _mat(6, synth.TAG_C, 23, n, kind="uniform")
     D = D0.copy()
-    impl(Y, np.eye(n), D)
+    impl(Y, eye(n), D)
     assert_bitwise(D, D0 + Y, "B = I")
 
 
@@ -83,14 +138,14 @@ def pin_column_sums(impl):
     _, B = _mat(7, synth.TAG_B, K, N)
     _, C0 = _mat(7, synth.TAG_C, M, N)
     C = C0.copy()
-    impl(np.ones((M, K)), B, C)
-    want = C0 + B.astype(np.int64).sum(axis=0)[None, :].astype(np.float64)
+    impl(ones((M, K)), B, C)
+    want = C0 + B.astype(np.int64).sum(axis=0)[None, :].astype(DT)
     assert_bitwise(C, want, "column sums")
     # and B = ones: row sums of A
     _, A = _mat(8, synth.TAG_A, M, K)
     C = C0.copy()
-    impl(A, np.ones((K, N)), C)
-    want = C0 + A.astype(np.int64).sum(axis=1)[:, None].astype(np.float64)
+    impl(A, ones((K, N)), C)
+    want = C0 + A.astype(np.int64).sum(axis=1)[:, None].astype(DT)
     assert_bitwise(C, want, "row sums")
 
 
@@ -111,17 +166,17 @@ def pin_one_hot_index(impl):
     M, N, K = 6, 11, 8
     _, B = _mat(10, synth.TAG_B, K, N)
     for (i0, k0) in [(0, 0), (5, 7), (2, 6), (4, 1)]:
-        A = np.zeros((M, K)); A[i0, k0] = 1.0
-        C = np.zeros((M, N))
+        A = zeros((M, K)); A[i0, k0] = 1.0
+        C = zeros((M, N))
         impl(A, B, C)
-        want = np.zeros((M, N)); want[i0, :] = B[k0, :]
+        want = zeros((M, N)); want[i0, :] = B[k0, :]
         assert_bitwise(C, want, "one-hot A at %s" % ((i0, k0),))
     _, A = _mat(10, synth.TAG_A, M, K)
     for (k0, j0) in [(0, 0), (7, 10), (3, 9)]:
-        Bh = np.zeros((K, N)); Bh[k0, j0] = 1.0
-        C = np.zeros((M, N))
+        Bh = zeros((K, N)); Bh[k0, j0] = 1.0
+        C = zeros((M, N))
         impl(A, Bh, C)
-        want = np.zeros((M, N)); want[:, j0] = A[:, k0]
+        want = zeros((M, N)); want[:, j0] = A[:, k0]
         assert_bitwise(C, want, "one-hot B at %s" % ((k0, j0),))
 
 
@@ -149,12 +204,12 @@ def pin_tiny_exact(impl, limit=5):
             for K in range(limit + 1):
                 for kind in ("int", "dyadic"):
                     k = "int" if kind == "int" else "uniform"
-                    Ab, A = synth.matrix(seed, synth.TAG_A, M, K, K + 2, k)
-                    Bb, B = synth.matrix(seed, synth.TAG_B, K, N, N + 3, k)
-                    Cb, C = synth.matrix(seed, synth.TAG_C, M, N, N + 1, k)
+                    Ab, A = synth.matrix(seed, synth.TAG_A, M, K, K + 2, k, DT)
+                    Bb, B = synth.matrix(seed, synth.TAG_B, K, N, N + 3, k, DT)
+                    Cb, C = synth.matrix(seed, synth.TAG_C, M, N, N + 1, k, DT)
                     if kind == "dyadic":
                         for X in (A, B, C):
-                            X[...] = np.round(X * 1024.0) / 1024.0
+                            X[...] = (np.round(X.astype(np.float64) * 1024.0) / 1024.0).astype(DT)
                     C0 = C.copy()
                     impl(A, B, C)
                     want = _exact(A, B, C0)
@@ -173,24 +228,24 @@ def rounded_sequence(A, B, C0):
     p = RN(a*b), c = RN(c + p), k ascending, starting from c_in (Section 2.1 loop body)."""
     M, K = A.shape
     N = B.shape[1]
-    out = np.empty((M, N))
+    out = np.empty((M, N), dtype=DT)
     for i in range(M):
         for j in range(N):
             c = float(C0[i, j])
             for k in range(K):
-                p = float(Fraction(float(A[i, k])) * Fraction(float(B[k, j])))
-                c = float(Fraction(c) + Fraction(p))
+                p = rn(Fraction(float(A[i, k])) * Fraction(float(B[k, j])))
+                c = rn(Fraction(c) + Fraction(p))
             out[i, j] = c
     return out
 
 
 def pin_rounded_sequence(impl):
     """Full-precision random doubles: the definition fixes every rounding, so the result is bitwise
-    the emulated sequence.  float(Fraction) is correctly rounded (round-half-even)."""
+    the emulated sequence.  rn() rounds an exact rational to the nearest value, ties to even."""
     for t, (M, N, K) in enumerate([(3, 4, 7), (2, 9, 33), (5, 3, 64)]):
-        _, A = synth.matrix(100 + t, synth.TAG_A, M, K, K + 1, "uniform")
-        _, B = synth.matrix(100 + t, synth.TAG_B, K, N, N + 2, "uniform")
-        _, C = synth.matrix(100 + t, synth.TAG_C, M, N, N + 5, "uniform")
+        _, A = synth.matrix(100 + t, synth.TAG_A, M, K, K + 1, "uniform", DT)
+        _, B = synth.matrix(100 + t, synth.TAG_B, K, N, N + 2, "uniform", DT)
+        _, C = synth.matrix(100 + t, synth.TAG_C, M, N, N + 5, "uniform", DT)
         want = rounded_sequence(A, B, C.copy())
         impl(A, B, C)
         assert_bitwise(C, want, "rounded sequence %s" % ((M, N, K),))
@@ -198,7 +253,8 @@ def pin_rounded_sequence(impl):
 
 def pin_rounding_cases(impl):
     """Hand-derived binary64 cases: unfused product, ascending k, start from c_in, ties to even."""
-    with open(os.path.join(GOLDEN, "rounding_cases.txt")) as f:
+    fixture = "rounding_cases_f32.txt" if DT == np.float32 else "rounding_cases.txt"
+    with open(os.path.join(GOLDEN, fixture)) as f:
         for line in f:
             if not line.strip() or line.startswith("#"):
                 continue
@@ -208,24 +264,24 @@ def pin_rounding_cases(impl):
             K = len(a)
             assert len(b) == K
             # embed the case at position (1, 2) of a 3x4 problem; other entries are zero
-            A = np.zeros((3, K)); B = np.zeros((K, 4)); C = np.zeros((3, 4))
+            A = zeros((3, K)); B = zeros((K, 4)); C = zeros((3, 4))
             A[1, :] = a; B[:, 2] = b; C[1, 2] = float.fromhex(cin)
             impl(A, B, C)
-            w = np.zeros((3, 4)); w[1, 2] = float.fromhex(want)
+            w = zeros((3, 4)); w[1, 2] = float.fromhex(want)
             assert_bitwise(C, w, "rounding case " + name)
 
 
 # ------------------------------------------------------------ integer exactness
 
 def pin_integer_exact(impl, shape=(256, 256, 256), lds=None, seed=0):
-    """Entries in {-4..4}: |sum| <= 16 K + 4 << 2^53, so every partial sum is an exact integer in any
-    order; the result must equal int64 arithmetic bit for bit."""
+    """Entries in {-4..4}: |sum| <= 16 K + 4, far below 2^53 (and below 2^24 for K < 2^20), so every
+    partial sum is an exact integer in any order; the result must equal int64 arithmetic bit for bit."""
     M, N, K = shape
     lda, ldb, ldc = lds or (K, N, N)
-    Ab, A = synth.matrix(seed, synth.TAG_A, M, K, lda, "int")
-    Bb, B = synth.matrix(seed, synth.TAG_B, K, N, ldb, "int")
-    Cb, C = synth.matrix(seed, synth.TAG_C, M, N, ldc, "int")
-    want = (C.astype(np.int64) + A.astype(np.int64) @ B.astype(np.int64)).astype(np.float64)
+    Ab, A = synth.matrix(seed, synth.TAG_A, M, K, lda, "int", DT)
+    Bb, B = synth.matrix(seed, synth.TAG_B, K, N, ldb, "int", DT)
+    Cb, C = synth.matrix(seed, synth.TAG_C, M, N, ldc, "int", DT)
+    want = (C.astype(np.int64) + A.astype(np.int64) @ B.astype(np.int64)).astype(DT)
     impl(A, B, C)
     assert_bitwise(C, want, "integer exact %s" % (shape,))
     assert synth.padding_intact(Ab, K) and synth.padding_intact(Bb, N) and synth.padding_intact(Cb, N)
@@ -235,14 +291,14 @@ def pin_integer_exact(impl, shape=(256, 256, 256), lds=None, seed=0):
 
 def pin_error_bound(impl, shape=(256, 256, 256), samples=300, seed=0):
     """Uniform[-1,1) inputs: against the exactly rounded value, the recursive-summation bound
-    |c_hat - c| <= gamma_{K+1} (|c_in| + S_ij), gamma_n = n u / (1 - n u), u = 2^-53, must hold."""
+    |c_hat - c| <= gamma_{K+1} (|c_in| + S_ij), gamma_n = n u / (1 - n u), u = 2^-53 (2^-24 in float32), must hold."""
     M, N, K = shape
-    _, A = synth.matrix(seed, synth.TAG_A, M, K, None, "uniform")
-    _, B = synth.matrix(seed, synth.TAG_B, K, N, None, "uniform")
-    _, C = synth.matrix(seed, synth.TAG_C, M, N, None, "uniform")
+    _, A = synth.matrix(seed, synth.TAG_A, M, K, None, "uniform", DT)
+    _, B = synth.matrix(seed, synth.TAG_B, K, N, None, "uniform", DT)
+    _, C = synth.matrix(seed, synth.TAG_C, M, N, None, "uniform", DT)
     C0 = C.copy()
     impl(A, B, C)
-    u = Fraction(1, 2 ** 53)
+    u = Fraction(1, 2 ** mant_bits())
     gamma = (K + 1) * u / (1 - (K + 1) * u)
     rng = np.random.default_rng(seed + 1)
     pts = {(0, 0), (M - 1, N - 1), (0, N - 1), (M - 1, 0)}
@@ -269,9 +325,9 @@ def pin_block_split_invariance(impl, bitwise_k=True):
     continues the same ascending sequence, so it is bitwise too for an implementation that follows
     the definition's order (bitwise_k=False relaxes that to the tolerance for other orders)."""
     M, N, K = 21, 34, 77
-    _, A = synth.matrix(21, synth.TAG_A, M, K, K + 3, "uniform")
-    _, B = synth.matrix(21, synth.TAG_B, K, N, N + 6, "uniform")
-    _, C0 = synth.matrix(21, synth.TAG_C, M, N, N + 2, "uniform")
+    _, A = synth.matrix(21, synth.TAG_A, M, K, K + 3, "uniform", DT)
+    _, B = synth.matrix(21, synth.TAG_B, K, N, N + 6, "uniform", DT)
+    _, C0 = synth.matrix(21, synth.TAG_C, M, N, N + 2, "uniform", DT)
     whole = C0.copy(); impl(A, B, whole)
     parts = C0.copy()
     for (r0, r1) in [(0, 8), (8, 21)]:
@@ -284,21 +340,22 @@ def pin_block_split_invariance(impl, bitwise_k=True):
     if bitwise_k:
         assert_bitwise(ks, whole, "k split")
     else:
-        S = np.abs(A) @ np.abs(B)
-        assert np.all(np.abs(ks - whole) <= 1e-13 * S)
+        S = _abs_product(A, B)
+        tol = 2.0 ** -19 if DT == np.float32 else 1e-13
+        assert np.all(np.abs(ks.astype(np.float64) - whole) <= tol * S)
 
 
 def pin_ld_independence(impl):
     """The result does not depend on the leading dimensions; padding is neither read (the NaN
     sentinel would leak) nor written."""
     M, N, K = 13, 27, 31
-    _, A = synth.matrix(31, synth.TAG_A, M, K, None, "uniform")
-    _, B = synth.matrix(31, synth.TAG_B, K, N, None, "uniform")
-    _, C0 = synth.matrix(31, synth.TAG_C, M, N, None, "uniform")
+    _, A = synth.matrix(31, synth.TAG_A, M, K, None, "uniform", DT)
+    _, B = synth.matrix(31, synth.TAG_B, K, N, None, "uniform", DT)
+    _, C0 = synth.matrix(31, synth.TAG_C, M, N, None, "uniform", DT)
     dense = C0.copy(); impl(A, B, dense)
-    Ab, Ap = synth.matrix(31, synth.TAG_A, M, K, K + 9, "uniform")
-    Bb, Bp = synth.matrix(31, synth.TAG_B, K, N, N + 4, "uniform")
-    Cb, Cp = synth.matrix(31, synth.TAG_C, M, N, N + 7, "uniform")
+    Ab, Ap = synth.matrix(31, synth.TAG_A, M, K, K + 9, "uniform", DT)
+    Bb, Bp = synth.matrix(31, synth.TAG_B, K, N, N + 4, "uniform", DT)
+    Cb, Cp = synth.matrix(31, synth.TAG_C, M, N, N + 7, "uniform", DT)
     impl(Ap, Bp, Cp)
     assert not np.isnan(Cp).any(), "NaN padding leaked into C"
     assert_bitwise(Cp, dense, "ld independence")
@@ -307,12 +364,12 @@ def pin_ld_independence(impl):
 
 def pin_degenerate(impl):
     """M*N = 0 is a no-op; K = 0 leaves C unchanged."""
-    _, C0 = synth.matrix(41, synth.TAG_C, 4, 6, 8, "uniform")
+    _, C0 = synth.matrix(41, synth.TAG_C, 4, 6, 8, "uniform", DT)
     C = C0.copy()
-    impl(np.zeros((4, 0)), np.zeros((0, 6)), C)
+    impl(zeros((4, 0)), zeros((0, 6)), C)
     assert_bitwise(C, C0, "K = 0")
-    impl(np.zeros((0, 5)), np.zeros((5, 6)), np.zeros((0, 6)))
-    impl(np.zeros((4, 5)), np.zeros((5, 0)), np.zeros((4, 0)))
+    impl(zeros((0, 5)), zeros((5, 6)), zeros((0, 6)))
+    impl(zeros((4, 5)), zeros((5, 0)), zeros((4, 0)))
 
 
 ORDER_DEPENDENT = [pin_rounded_sequence, pin_rounding_cases]
