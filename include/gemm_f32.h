@@ -1,0 +1,56 @@
+/*
+ * gemm_f32.h -- single-precision entry points of libgemm_f64.so (AMD MI355X, gfx950).
+ *
+ * The paper derives SGEMM from its DGEMM by substituting f32 for f64 in the operand types and
+ * doubling the elements per vector register (Section 2.13, "SGEMM performance"); the operation is
+ * the loop nest of Section 2.1 on float buffers:
+ *
+ *      C[i*ldc + j] += sum_{k=0}^{K-1} A[i*lda + k] * B[k*ldb + j],   0 <= i < M, 0 <= j < N.
+ *
+ * Everything stated in gemm_f64.h about argument meaning, layout, ownership, asynchrony, aliasing,
+ * edge handling and error behaviour holds here with `float` for `double`; the return codes are the
+ * GEMM_F64_* values of that header.  Differences:
+ *   - pointers must be 4-byte aligned; the asynchronous 16-byte global->LDS path needs 16-byte
+ *     aligned A and B and lda, ldb that are multiples of 4, otherwise a slower register-staged
+ *     variant of the same kernel runs (same result);
+ *   - arithmetic is binary32 throughout (FP32 MFMA, four k per instruction, accumulated from zero,
+ *     C added once at the end): bit-identical to the sequential binary32 nest whenever every
+ *     partial sum is exact (e.g. integer data with |sum| < 2^24), and within
+ *     2^-19 * sum_k |a_ik * b_kj| of it elementwise otherwise (both are within the recursive
+ *     summation bound of the exact result; the typical difference is about 2^-24 of that scale).
+ */
+#ifndef GEMM_F32_H
+#define GEMM_F32_H
+
+#include <stdint.h>
+
+#include "gemm_f64.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Enqueue C += A * B (float, device pointers, row-major, leading dimensions in elements) on `stream`. */
+int gemm_f32(int64_t M, int64_t N, int64_t K,
+             const float *A, int64_t lda,
+             const float *B, int64_t ldb,
+             float *C, int64_t ldc,
+             void *stream);
+
+/* The same with an explicit kernel variant (-1 = automatic), as gemm_f64_ex. */
+int gemm_f32_ex(int64_t M, int64_t N, int64_t K,
+                const float *A, int64_t lda,
+                const float *B, int64_t ldb,
+                float *C, int64_t ldc,
+                void *stream, int variant);
+
+/* Variant table of the float kernels ("mfma_128x128x32", ...) and the host-side selection rule
+ * (the analogue of choosing M_C, K_C, M_R, N_R per element type in Section 2.13). */
+int gemm_f32_variant_count(void);
+const char *gemm_f32_variant_name(int variant);
+int gemm_f32_choose_variant(int64_t M, int64_t N, int64_t K, int num_cu);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GEMM_F32_H */

@@ -47,6 +47,16 @@ def load():
     lib.gemm_f64_strerror.restype = ctypes.c_char_p
     lib.gemm_f64_version.argtypes = []
     lib.gemm_f64_version.restype = ci
+    lib.gemm_f32.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
+    lib.gemm_f32.restype = ci
+    lib.gemm_f32_ex.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, ci]
+    lib.gemm_f32_ex.restype = ci
+    lib.gemm_f32_variant_count.argtypes = []
+    lib.gemm_f32_variant_count.restype = ci
+    lib.gemm_f32_variant_name.argtypes = [ci]
+    lib.gemm_f32_variant_name.restype = ctypes.c_char_p
+    lib.gemm_f32_choose_variant.argtypes = [i64, i64, i64, ci]
+    lib.gemm_f32_choose_variant.restype = ci
     _lib = lib
     return lib
 
@@ -113,6 +123,34 @@ def gemm_f64_tile_of_block(block, tiles_m, tiles_n):
 
 def gemm_f64_version() -> int:
     return int(load().gemm_f64_version())
+
+
+# ---- single precision (include/gemm_f32.h) ------------------------------------------------------
+
+def gemm_f32(M, N, K, A, lda, B, ldb, C, ldc, stream=None):
+    """Enqueue float C += A @ B (device pointers, row-major, leading dimensions in elements)."""
+    _check(load().gemm_f32(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _stream(stream)))
+
+
+def gemm_f32_ex(M, N, K, A, lda, B, ldb, C, ldc, stream=None, variant=-1):
+    _check(load().gemm_f32_ex(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _stream(stream), int(variant)))
+
+
+def gemm_f32_raw(M, N, K, A, lda, B, ldb, C, ldc, stream=0, variant=-1) -> int:
+    return int(load().gemm_f32_ex(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, stream, int(variant)))
+
+
+def gemm_f32_variant_count() -> int:
+    return int(load().gemm_f32_variant_count())
+
+
+def gemm_f32_variant_name(variant: int):
+    s = load().gemm_f32_variant_name(int(variant))
+    return None if s is None else s.decode()
+
+
+def gemm_f32_choose_variant(M, N, K, num_cu=256) -> int:
+    return int(load().gemm_f32_choose_variant(M, N, K, int(num_cu)))
 
 
 def variant_index(name: str) -> int:

@@ -5,9 +5,10 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgemm_f64.so")
-SOURCES = [os.path.join(CSRC, "gemm_f64.hip")]
-DEPENDS = SOURCES + [os.path.join(CSRC, "gemm_f64_mfma.hpp"),
-                     os.path.join(os.path.dirname(HERE), "include", "gemm_f64.h")]
+SOURCES = [os.path.join(CSRC, "gemm_f64.hip"), os.path.join(CSRC, "gemm_f32.hip")]
+DEPENDS = SOURCES + [os.path.join(CSRC, "gemm_mfma.hpp"), os.path.join(CSRC, "gemm_host.hpp"),
+                     os.path.join(os.path.dirname(HERE), "include", "gemm_f64.h"),
+                     os.path.join(os.path.dirname(HERE), "include", "gemm_f32.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

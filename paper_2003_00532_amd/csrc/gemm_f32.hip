@@ -1,0 +1,44 @@
+// libgemm_f64.so, single-precision entry points (declared and documented in include/gemm_f32.h).
+#include "../../include/gemm_f32.h"
+
+#include "gemm_host.hpp"
+
+using namespace gemm_detail;
+
+namespace {
+// Index order is part of the ABI of gemm_f32_ex.  One LDS stage holds 32 values of k in float.
+// Efficiencies: measured fractions of the FP32 MFMA peak at 8192^3 on MI355X.
+const Variant kVariants[] = {
+    {"naive", 0, 0, 0.0},
+    {"mfma_128x128x32", 128, 128, 0.955},
+    {"mfma_64x64x32", 64, 64, 0.915},
+    {"mfma_128x64x32", 128, 64, 0.935},
+    {"mfma_64x128x32", 64, 128, 0.965},
+};
+constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+}  // namespace
+
+extern "C" int gemm_f32_variant_count(void) { return kNumVariants; }
+
+extern "C" const char *gemm_f32_variant_name(int variant)
+{
+    return (variant >= 0 && variant < kNumVariants) ? kVariants[variant].name : nullptr;
+}
+
+extern "C" int gemm_f32_choose_variant(int64_t M, int64_t N, int64_t K, int num_cu)
+{
+    (void)K;
+    return choose_variant(kVariants, kNumVariants, M, N, num_cu);
+}
+
+extern "C" int gemm_f32_ex(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
+                           float *C, int64_t ldc, void *stream, int variant)
+{
+    return gemm_ex<float>(kVariants, kNumVariants, M, N, K, A, lda, B, ldb, C, ldc, stream, variant);
+}
+
+extern "C" int gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
+                        float *C, int64_t ldc, void *stream)
+{
+    return gemm_f32_ex(M, N, K, A, lda, B, ldb, C, ldc, stream, -1);
+}

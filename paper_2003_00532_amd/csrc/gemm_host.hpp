@@ -1,0 +1,147 @@
+// Host side shared by the double and float entry points: argument checks, the tile-quantisation
+// model that picks a kernel variant, launches.  The C ABIs are declared in include/gemm_f64.h and
+// include/gemm_f32.h; return codes are the GEMM_F64_* values for both.
+#pragma once
+#include "../../include/gemm_f64.h"
+
+#include <hip/hip_runtime.h>
+
+#include "gemm_mfma.hpp"
+
+namespace gemm_detail {
+
+struct Variant {
+    const char *name;
+    int bm, bn;  // macro-tile; 0 for the untiled kernel
+    // measured fraction of the MFMA peak reached by this tile shape on a large square problem,
+    // used by the selection model
+    double efficiency;
+};
+
+// A compute unit that holds a single workgroup has nothing to run while that workgroup waits at its
+// barrier or in its prologue/epilogue (measured: 2048^3 fp64 as 256 tiles of 128x128 reaches 80 %).
+constexpr double kSingleWorkgroupPenalty = 0.84;
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Tile quantisation model: workgroups are spread over the compute units, so the makespan is about
+// ceil(tiles / CUs) macro-tiles of work per CU; a smaller tile wastes less at the edges and balances
+// better but runs its inner loop a little less efficiently.  Variant 0 (untiled) is never chosen.
+inline int choose_variant(const Variant *variants, int count, int64_t M, int64_t N, int num_cu)
+{
+    if (num_cu < 1) num_cu = 1;
+    if (M <= 0 || N <= 0) return 1;
+    int best = 1;
+    double best_cost = 0.0;
+    for (int v = 1; v < count; ++v) {
+        const Variant &var = variants[v];
+        const int64_t tiles = ceil_div(M, var.bm) * ceil_div(N, var.bn);
+        const double eff = var.efficiency * (tiles <= num_cu ? kSingleWorkgroupPenalty : 1.0);
+        const double cost = (double)ceil_div(tiles, num_cu) * var.bm * var.bn / eff;
+        if (v == 1 || cost < best_cost) {
+            best = v;
+            best_cost = cost;
+        }
+    }
+    return best;
+}
+
+template <typename T>
+int validate(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B, int64_t ldb, const T *C,
+             int64_t ldc)
+{
+    if (M < 0 || N < 0 || K < 0) return GEMM_F64_ERR_DIM;
+    if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
+    if (lda < (K > 1 ? K : 1)) return GEMM_F64_ERR_LDA;
+    if (ldb < (N > 1 ? N : 1)) return GEMM_F64_ERR_LDB;
+    if (ldc < (N > 1 ? N : 1)) return GEMM_F64_ERR_LDC;
+    const bool c_live = M > 0 && N > 0;
+    const bool ab_live = c_live && K > 0;
+    if (c_live && C == nullptr) return GEMM_F64_ERR_NULL;
+    if (ab_live && (A == nullptr || B == nullptr)) return GEMM_F64_ERR_NULL;
+    const uintptr_t mask = sizeof(T) - 1;
+    if (c_live && ((uintptr_t)C & mask)) return GEMM_F64_ERR_ALIGN;
+    if (ab_live && (((uintptr_t)A & mask) || ((uintptr_t)B & mask))) return GEMM_F64_ERR_ALIGN;
+    return GEMM_F64_OK;
+}
+
+// 16-byte global->LDS copies need 16-byte aligned bases and leading dimensions that are multiples of
+// the elements per 16 bytes; their per-lane byte offsets (up to 128 rows of A, a few rows of B) are
+// 32-bit, which bounds the leading dimensions.
+template <typename T>
+bool async_copies_possible(const T *A, int64_t lda, const T *B, int64_t ldb)
+{
+    constexpr int64_t E = 16 / sizeof(T);
+    return (((uintptr_t)A | (uintptr_t)B) & 15u) == 0 && (lda % E == 0) && (ldb % E == 0) && lda < (1 << 20) &&
+           ldb < (1 << 20);
+}
+
+template <typename T, int BM, int BN, int WM, int WN>
+hipError_t launch_mfma(int M, int N, int K, const T *A, int64_t lda, const T *B, int64_t ldb, T *C, int64_t ldc,
+                       hipStream_t stream)
+{
+    constexpr int BK = 8 * (16 / (int)sizeof(T));
+    const int tiles_m = (int)ceil_div(M, BM), tiles_n = (int)ceil_div(N, BN);
+    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(kThreads);
+    const bool vec = async_copies_possible(A, lda, B, ldb);
+    // The lean kernel assumes full tiles everywhere, whole K stages and aligned operands.
+    const bool lean = vec && (M % BM == 0) && (N % BN == 0) && (K % BK == 0);
+    if (lean)
+        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kLean>), grid, block, 0, stream, M, N, K, A, lda, B,
+                           ldb, C, ldc, tiles_m, tiles_n);
+    else if (vec)
+        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kGeneric>), grid, block, 0, stream, M, N, K, A, lda, B,
+                           ldb, C, ldc, tiles_m, tiles_n);
+    else
+        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kStaged>), grid, block, 0, stream, M, N, K, A, lda, B,
+                           ldb, C, ldc, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_naive(int M, int N, int K, const T *A, int64_t lda, const T *B, int64_t ldb, T *C, int64_t ldc,
+                        hipStream_t stream)
+{
+    const int64_t total = (int64_t)M * N;
+    const dim3 grid((unsigned)ceil_div(total, 256)), block(256);
+    hipLaunchKernelGGL(gemm_naive_kernel<T>, grid, block, 0, stream, M, N, K, A, lda, B, ldb, C, ldc);
+    return hipGetLastError();
+}
+
+inline int current_cu_count()
+{
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+        return v;
+    return 256;
+}
+
+// The body common to gemm_f64_ex and gemm_f32_ex.
+template <typename T>
+int gemm_ex(const Variant *variants, int count, int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
+            int64_t ldb, T *C, int64_t ldc, void *stream_, int variant)
+{
+    const int rc = validate(M, N, K, A, lda, B, ldb, C, ldc);
+    if (rc != GEMM_F64_OK) return rc;
+    if (variant < -1 || variant >= count) return GEMM_F64_ERR_VARIANT;
+    if (M == 0 || N == 0 || K == 0) return GEMM_F64_OK;
+    hipStream_t stream = (hipStream_t)stream_;
+    if (variant == -1) variant = choose_variant(variants, count, M, N, current_cu_count());
+    const int m = (int)M, n = (int)N, k = (int)K;
+    hipError_t err = hipSuccess;
+    switch (variant) {
+    case 0:
+        if (ceil_div(M * N, 256) > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
+        err = launch_naive<T>(m, n, k, A, lda, B, ldb, C, ldc, stream);
+        break;
+    case 1: err = launch_mfma<T, 128, 128, 2, 2>(m, n, k, A, lda, B, ldb, C, ldc, stream); break;
+    case 2: err = launch_mfma<T, 64, 64, 2, 2>(m, n, k, A, lda, B, ldb, C, ldc, stream); break;
+    case 3: err = launch_mfma<T, 128, 64, 2, 2>(m, n, k, A, lda, B, ldb, C, ldc, stream); break;
+    case 4: err = launch_mfma<T, 64, 128, 2, 2>(m, n, k, A, lda, B, ldb, C, ldc, stream); break;
+    default: return GEMM_F64_ERR_VARIANT;
+    }
+    return err == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
+}
+
+}  // namespace gemm_detail

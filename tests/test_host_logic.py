@@ -18,14 +18,14 @@ def declared_functions():
         if fn.endswith(".h"):
             text = open(os.path.join(inc, fn)).read()
             text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-            names += re.findall(r"\b(gemm_f64\w*)\s*\(", text)
+            names += re.findall(r"\b(gemm_f(?:64|32)\w*)\s*\(", text)
     return sorted(set(names))
 
 
 def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(binding.LIB_PATH)
     names = declared_functions()
-    assert "gemm_f64" in names and "gemm_f64_ex" in names and len(names) >= 8
+    assert "gemm_f64" in names and "gemm_f64_ex" in names and "gemm_f32" in names and len(names) >= 13
     for n in names:
         assert hasattr(lib, n), "libgemm_f64.so does not export " + n
     for n in names:
@@ -104,6 +104,24 @@ def test_variant_selection_follows_tile_quantisation():
     for (M, N, K) in [(1, 1, 1), (256, 256, 256), (2048, 2048, 2048), (16384, 16384, 256), (100000, 3, 7)]:
         v = binding.gemm_f64_choose_variant(M, N, K, 256)
         assert 1 <= v < binding.gemm_f64_variant_count()
+
+
+def test_single_precision_entry_points_validate_like_the_double_ones():
+    p = 0x1000
+    raw = binding.gemm_f32_raw
+    assert raw(-1, 2, 2, p, 2, p, 2, p, 2) == -1
+    assert raw(2, 2, 3, p, 2, p, 2, p, 2) == -2
+    assert raw(2, 3, 2, p, 2, p, 2, p, 3) == -3
+    assert raw(2, 3, 2, p, 2, p, 3, p, 2) == -4
+    assert raw(2, 2, 2, None, 2, p, 2, p, 2) == -5
+    assert raw(2, 2, 2, p + 2, 2, p, 2, p, 2) == -6     # 4-byte alignment is enough, 2 is not
+    assert raw(2, 2, 2, p, 2, p, 2, p, 2, variant=99) == -9
+    assert raw(0, 5, 5, None, 5, None, 5, None, 5) == 0
+    n = binding.gemm_f32_variant_count()
+    names = [binding.gemm_f32_variant_name(v) for v in range(n)]
+    assert names[0] == "naive" and all(nm.endswith("x32") for nm in names[1:])
+    for (M, N, K) in [(1, 1, 1), (2048, 2048, 2048), (8192, 8192, 8192), (2088, 2049, 2047)]:
+        assert 1 <= binding.gemm_f32_choose_variant(M, N, K, 256) < n
 
 
 def test_gflops_convention_matches_the_papers_printed_numbers():
