@@ -5,9 +5,10 @@ A step is one call of gemm_f64 (C += A B through the C ABI) on the named workloa
 already resident in HBM.  Prints ONE JSON line on stdout: DGEMM GFLOP/s = 2 M N K / t / 1e9 (the
 paper's convention, Section 1.3), the roofline of the kernel (FP64 MFMA, 78.6 TFLOP/s published
 peak; per-launch duration measured with HIP events on the launch stream) and the CPU oracle timed on
-a bounded sample of the same workload.  Diagnostics go to stderr.
+a bounded sample of the same workload.  Diagnostics go to stderr.  With --dtype f32 the same is
+done for the single-precision path (gemm_f32, FP32 MFMA peak 157.3 TFLOP/s, float32 oracle).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_8192] [--variant -1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_8192] [--variant -1] [--dtype f64|f32]
     python bench.py --copy-calibration     # plain device copy of known size, for scaling rocprof counters
 """
 import argparse
@@ -21,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP64_MFMA_TFLOPS = 78.6   # MI355X published dense FP64 matrix peak (256 CU x 128 flop/clk x 2.4 GHz)
+PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X published dense FP32 matrix peak
 PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), scaled
@@ -30,6 +32,8 @@ MEASURED_TRAFFIC_BYTES = {
     ("c3_8192", "mfma_128x128x16"): (6688540 * 2.0 + 524288 * 1.0) * 1024,
     # profiles/mfma_64x128x16_c3_8192_pmc.txt: FETCH_SIZE 8 739 400 KiB x 2.0 + WRITE_SIZE 524 288 KiB x 1.0
     ("c3_8192", "mfma_64x128x16"): (8739400 * 2.0 + 524288 * 1.0) * 1024,
+    # profiles/sgemm_mfma_64x128x32_c3_8192_pmc.txt: FETCH_SIZE 4 346 210 KiB x 2.0 + WRITE_SIZE 262 265 KiB x 1.0
+    ("c3_8192", "mfma_64x128x32"): (4346210 * 2.0 + 262265 * 1.0) * 1024,
 }
 
 
@@ -37,20 +41,22 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(w, seed, target_seconds=12.0):
+def cpu_baseline(w, seed, target_seconds=12.0, np_dtype=None):
     """Time the CPU oracle, as it stands, on complete rows of the same workload (all host threads)."""
     import numpy as np
     import oracle
     from paper_2003_00532_amd import synth
 
+    np_dtype = np.float64 if np_dtype is None else np_dtype
+    ref = oracle.gemm_f32_ref if np_dtype == np.float32 else oracle.gemm_f64_ref
     threads = oracle.ref_threads()
-    _, B = synth.matrix(seed, synth.TAG_B, w.K, w.N, w.ldb, "uniform")
+    _, B = synth.matrix(seed, synth.TAG_B, w.K, w.N, w.ldb, "uniform", np_dtype)
 
     def run(rows):
-        A = np.empty((rows, w.K)); synth.fill(A, seed, synth.TAG_A, "uniform")
-        C = np.empty((rows, w.N)); synth.fill(C, seed, synth.TAG_C, "uniform" if w.c_kind == "uniform" else "zeros")
+        A = np.empty((rows, w.K), np_dtype); synth.fill(A, seed, synth.TAG_A, "uniform")
+        C = np.empty((rows, w.N), np_dtype); synth.fill(C, seed, synth.TAG_C, "uniform" if w.c_kind == "uniform" else "zeros")
         t0 = time.perf_counter()
-        oracle.gemm_f64_ref(A, B, C)
+        ref(A, B, C)
         return time.perf_counter() - t0
 
     pilot_rows = min(w.M, 4 * threads)
@@ -85,6 +91,7 @@ def main():
     ap.add_argument("--workload", default="c3_8192")
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--dtype", choices=["f64", "f32"], default="f64")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true")
     args = ap.parse_args()
@@ -105,23 +112,32 @@ def main():
         copy_calibration()
         return
 
+    import numpy as np
+    f32 = args.dtype == "f32"
+    np_dtype = np.float32 if f32 else np.float64
+    gemm_ex = binding.gemm_f32_ex if f32 else binding.gemm_f64_ex
+    choose = binding.gemm_f32_choose_variant if f32 else binding.gemm_f64_choose_variant
+    variant_name = binding.gemm_f32_variant_name if f32 else binding.gemm_f64_variant_name
+    peak = PEAK_FP32_MFMA_TFLOPS if f32 else PEAK_FP64_MFMA_TFLOPS
+    elem = 4 if f32 else 8
+
     w = synth.WORKLOADS[args.workload]
     dev = torch.device("cuda:0")
     t0 = time.perf_counter()
-    Ab, Bb, Cb = synth.workload_inputs(w, seed=args.seed)
+    Ab, Bb, Cb = synth.workload_inputs(w, seed=args.seed, dtype=np_dtype)
     dA, dB, dC = (torch.from_numpy(x).to(dev) for x in (Ab, Bb, Cb))
     del Ab, Bb, Cb
     torch.cuda.synchronize()
     log("inputs for %s generated and resident in HBM after %.1f s" % (w.name, time.perf_counter() - t0))
 
     props = torch.cuda.get_device_properties(0)
-    variant = args.variant if args.variant >= 0 else binding.gemm_f64_choose_variant(w.M, w.N, w.K, props.multi_processor_count)
-    vname = binding.gemm_f64_variant_name(variant)
+    variant = args.variant if args.variant >= 0 else choose(w.M, w.N, w.K, props.multi_processor_count)
+    vname = variant_name(variant)
 
     stream = torch.cuda.current_stream()
 
     def step():
-        binding.gemm_f64_ex(w.M, w.N, w.K, dA, w.lda, dB, w.ldb, dC, w.ldc, stream=stream, variant=args.variant)
+        gemm_ex(w.M, w.N, w.K, dA, w.lda, dB, w.ldb, dC, w.ldc, stream=stream, variant=args.variant)
 
     for _ in range(args.warmup):
         step()
@@ -145,9 +161,11 @@ def main():
     gflops = w.flops / (ms_per_step * 1e-3) / 1e9
     achieved_tflops = w.flops / (kernel_ms * 1e-3) / 1e12
     traffic = MEASURED_TRAFFIC_BYTES.get((w.name, vname))
+    alg_bytes = w.algorithmic_bytes * elem / 8.0
+    prec = "fp32" if f32 else "fp64"
 
     out = {
-        "metric": "DGEMM GFLOP/s (2MNK/t), 1 GPU",
+        "metric": "%sGEMM GFLOP/s (2MNK/t), 1 GPU" % ("S" if f32 else "D"),
         "value": round(gflops, 1),
         "unit": "GFLOP/s",
         "n_gpus": 1,
@@ -157,21 +175,21 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f64",
+        "dtype": args.dtype,
         "data": "synthetic",
-        "config": {"workload": "%s: fp64 row-major C += A*B, M=%d N=%d K=%d, lda=%d ldb=%d ldc=%d, A,B uniform[-1,1) seed %d, C %s"
-                               % (w.name, w.M, w.N, w.K, w.lda, w.ldb, w.ldc, args.seed, w.c_kind),
+        "config": {"workload": "%s: %s row-major C += A*B, M=%d N=%d K=%d, lda=%d ldb=%d ldc=%d, A,B uniform[-1,1) seed %d, C %s"
+                               % (w.name, prec, w.M, w.N, w.K, w.lda, w.ldb, w.ldc, args.seed, w.c_kind),
                    "kernel_variant": vname, "device": props.name, "compute_units": props.multi_processor_count},
-        "pct_of_fp64_mfma_peak": round(100.0 * gflops / (PEAK_FP64_MFMA_TFLOPS * 1e3), 2),
-        "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": PEAK_FP64_MFMA_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_FP64_MFMA_TFLOPS, 4),
+        "pct_of_%s_mfma_peak" % prec: round(100.0 * gflops / (peak * 1e3), 2),
+        "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": peak,
+                     "unit": "TFLOP/s", "frac": round(achieved_tflops / peak, 4),
                      "traffic": traffic, "kernel_ms": round(kernel_ms, 4),
                      "kernel_ms_min": round(min(per_launch_ms), 4), "kernel_ms_max": round(max(per_launch_ms), 4),
-                     "algorithmic_flops_per_launch": w.flops, "algorithmic_bytes_per_launch": w.algorithmic_bytes},
+                     "algorithmic_flops_per_launch": w.flops, "algorithmic_bytes_per_launch": alg_bytes},
     }
     if not args.no_cpu_baseline:
         t0 = time.perf_counter()
-        out["cpu_baseline"] = cpu_baseline(w, args.seed)
+        out["cpu_baseline"] = cpu_baseline(w, args.seed, np_dtype=np_dtype)
         log("cpu baseline took %.1f s" % (time.perf_counter() - t0))
     print(json.dumps(out), flush=True)
 
