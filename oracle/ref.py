@@ -30,6 +30,12 @@ def _load():
             fn = getattr(lib, name)
             fn.argtypes = [i64, i64, i64, dp, i64, dp, i64, dp, i64]
             fn.restype = ctypes.c_int
+        lib.gemm_f64_general_ref.argtypes = [ctypes.c_int, ctypes.c_int, i64, i64, i64, ctypes.c_double, dp, i64,
+                                             dp, i64, ctypes.c_double, dp, i64]
+        lib.gemm_f64_general_ref.restype = ctypes.c_int
+        lib.gemm_f32_general_ref.argtypes = [ctypes.c_int, ctypes.c_int, i64, i64, i64, ctypes.c_float, dp, i64,
+                                             dp, i64, ctypes.c_float, dp, i64]
+        lib.gemm_f32_general_ref.restype = ctypes.c_int
         lib.gemm_f64_ref_threads.restype = ctypes.c_int
         lib.gemm_f64_ref_set_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -93,6 +99,37 @@ def gemm_f32_ref_ijk(A, B, C):
 def gemm_f32_absref(A, B, S):
     """float64 S += |A| @ |B| for float32 operands: the tolerance scale."""
     return _call("gemm_f32_absref", A, B, S)
+
+
+def gemm_general_ref(transa, transb, alpha, A, B, beta, C):
+    """C <- alpha * op(A) @ op(B) + beta * C in place (oracle/gemm_general_ref.c); returns C.
+
+    A and B are the arrays as stored: A is (K, M) when transa, B is (N, K) when transb.  The element
+    type (float64 or float32) is taken from C; alpha and beta are converted to it.
+    """
+    f32 = C.dtype == np.float32
+    want = np.float32 if f32 else np.float64
+    assert A.dtype == want and B.dtype == want and C.dtype == want and C.flags.writeable
+    M, N = C.shape
+    K = A.shape[0] if transa else A.shape[1]
+    assert A.shape == ((K, M) if transa else (M, K)), "A shape"
+    assert B.shape == ((N, K) if transb else (K, N)), "B shape"
+    fn = getattr(_load(), "gemm_f32_general_ref" if f32 else "gemm_f64_general_ref")
+    rc = fn(int(bool(transa)), int(bool(transb)), M, N, K, float(want(alpha)), A.ctypes.data, _ld(A),
+            B.ctypes.data, _ld(B), float(want(beta)), C.ctypes.data, _ld(C))
+    if rc != 0:
+        raise ValueError("gemm_general_ref failed with code %d" % rc)
+    return C
+
+
+def general_scale(transa, transb, alpha, A, B, beta, C0):
+    """float64 S = |alpha| * |op(A)| @ |op(B)| + |beta * C0|: the scale of the elementwise tolerance of the
+    general operation, obtained by running the binary64 oracle on absolute values."""
+    S = np.abs(C0.astype(np.float64))
+    if beta == 0:
+        S = np.zeros(C0.shape, dtype=np.float64)  # C0 is not read then and may hold NaN
+    return gemm_general_ref(transa, transb, abs(float(alpha)), np.abs(A.astype(np.float64)),
+                            np.abs(B.astype(np.float64)), abs(float(beta)), np.ascontiguousarray(S))
 
 
 def raw(name):
