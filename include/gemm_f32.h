@@ -44,6 +44,24 @@ int gemm_f32_ex(int64_t M, int64_t N, int64_t K,
                 float *C, int64_t ldc,
                 void *stream, int variant);
 
+/*
+ * The full operation C <- alpha * op(A) * op(B) + beta * C in float (Section 2.15 Q4 and Section 2.2 of
+ * the paper, see gemm_f64_general for the argument meaning, the folding rules for alpha == 0, K == 0 and
+ * beta == 0, and the arithmetic of the scalar tail).  Tolerance against the term-by-term binary32
+ * evaluation: 2^-19 * (|alpha| * sum_k |opA(i,k) * opB(k,j)| + |beta * C_in|); bit-identical when every
+ * intermediate value is exact.
+ */
+int gemm_f32_general(int transa, int transb, int64_t M, int64_t N, int64_t K,
+                     float alpha, const float *A, int64_t lda,
+                     const float *B, int64_t ldb,
+                     float beta, float *C, int64_t ldc,
+                     void *stream);
+int gemm_f32_general_ex(int transa, int transb, int64_t M, int64_t N, int64_t K,
+                        float alpha, const float *A, int64_t lda,
+                        const float *B, int64_t ldb,
+                        float beta, float *C, int64_t ldc,
+                        void *stream, int variant);
+
 /* Variant table of the float kernels ("mfma_128x128x32", ...) and the host-side selection rule
  * (the analogue of choosing M_C, K_C, M_R, N_R per element type in Section 2.13). */
 int gemm_f32_variant_count(void);

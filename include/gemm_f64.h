@@ -26,9 +26,9 @@ extern "C" {
 /* Return codes (0 = success; on any error nothing has been launched). */
 enum {
     GEMM_F64_OK = 0,
-    GEMM_F64_ERR_DIM = -1,       /* M, N or K negative                                   */
-    GEMM_F64_ERR_LDA = -2,       /* lda < max(1, K)                                      */
-    GEMM_F64_ERR_LDB = -3,       /* ldb < max(1, N)                                      */
+    GEMM_F64_ERR_DIM = -1,       /* M, N or K negative, or a transpose flag other than 0/1 */
+    GEMM_F64_ERR_LDA = -2,       /* lda < max(1, stored row length of A): K, or M if transposed */
+    GEMM_F64_ERR_LDB = -3,       /* ldb < max(1, stored row length of B): N, or K if transposed */
     GEMM_F64_ERR_LDC = -4,       /* ldc < max(1, N)                                      */
     GEMM_F64_ERR_NULL = -5,      /* null pointer for an operand that has elements        */
     GEMM_F64_ERR_ALIGN = -6,     /* a pointer is not 8-byte aligned                      */
@@ -87,6 +87,54 @@ int gemm_f64_ex(int64_t M, int64_t N, int64_t K,
                 const double *B, int64_t ldb,
                 double *C, int64_t ldc,
                 void *stream, int variant);
+
+/*
+ * gemm_f64_general: the full operation that the paper names but does not study
+ * (Section 2.15 Q4: DGEMM is really C = alpha*A*B + beta*C, its own experiments
+ * fix alpha = beta = 1, the cases alpha, beta in {0, 1} fold away, and strides
+ * and transposes are layout maps on the operands -- Section 2.2, where
+ * (d0, d1) -> (d1, d0) is the transpose):
+ *
+ *      C[i*ldc + j] <- alpha * sum_{k<K} opA(i,k) * opB(k,j) + beta * C[i*ldc + j]
+ *
+ *   transa    0: A is M x K, opA(i,k) = A[i*lda + k], lda >= max(1,K);
+ *             1: A is stored transposed, K x M, opA(i,k) = A[k*lda + i], lda >= max(1,M).
+ *   transb    0: B is K x N, opB(k,j) = B[k*ldb + j], ldb >= max(1,N);
+ *             1: B is stored transposed, N x K, opB(k,j) = B[j*ldb + k], ldb >= max(1,K).
+ *   alpha, beta   host scalars, passed by value.
+ *   everything else as for gemm_f64 (device pointers, row-major, asynchronous on
+ *   `stream`, no allocation, no workspace, padding inside a row's ld span and
+ *   memory past the last logical element never touched).
+ *
+ * Folding: when alpha == 0 or K == 0, A and B are not read (they may be NULL)
+ * and C <- beta * C (nothing is launched when beta == 1; C is set to +0 when
+ * beta == 0).  When beta == 0, C is not read: it may hold anything, NaN
+ * included, and is overwritten.
+ *
+ * Arithmetic: the sum over k is accumulated from zero in the matrix unit, then
+ * t = alpha * sum and C = t + beta * C, each operation rounded on its own (no
+ * fused multiply-add in this tail); C = t when beta == 0.  With alpha = beta =
+ * 1 and no transposes this is gemm_f64 bit for bit.  Against the term-by-term
+ * evaluation with k ascending the result is bit-identical whenever every
+ * intermediate value is exact and within
+ * 1e-13 * (|alpha| * sum_k |opA(i,k) * opB(k,j)| + |beta * C_in|) otherwise.
+ *
+ * Transposed operands change only how panels are brought into LDS; all four
+ * combinations run the same MFMA kernel at the same speed class.  The 128-bit
+ * asynchronous path needs 16-byte aligned A and B and even lda, ldb.
+ */
+int gemm_f64_general(int transa, int transb, int64_t M, int64_t N, int64_t K,
+                     double alpha, const double *A, int64_t lda,
+                     const double *B, int64_t ldb,
+                     double beta, double *C, int64_t ldc,
+                     void *stream);
+
+/* gemm_f64_general with the kernel variant chosen by the caller (-1 = automatic), as gemm_f64_ex. */
+int gemm_f64_general_ex(int transa, int transb, int64_t M, int64_t N, int64_t K,
+                        double alpha, const double *A, int64_t lda,
+                        const double *B, int64_t ldb,
+                        double beta, double *C, int64_t ldc,
+                        void *stream, int variant);
 
 /* Number of kernel variants and their names ("mfma_128x128x16", ...; NULL if out of range). */
 int gemm_f64_variant_count(void);

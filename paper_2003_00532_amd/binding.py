@@ -57,6 +57,15 @@ def load():
     lib.gemm_f32_variant_name.restype = ctypes.c_char_p
     lib.gemm_f32_choose_variant.argtypes = [i64, i64, i64, ci]
     lib.gemm_f32_choose_variant.restype = ci
+    cd, cf = ctypes.c_double, ctypes.c_float
+    lib.gemm_f64_general.argtypes = [ci, ci, i64, i64, i64, cd, vp, i64, vp, i64, cd, vp, i64, vp]
+    lib.gemm_f64_general.restype = ci
+    lib.gemm_f64_general_ex.argtypes = [ci, ci, i64, i64, i64, cd, vp, i64, vp, i64, cd, vp, i64, vp, ci]
+    lib.gemm_f64_general_ex.restype = ci
+    lib.gemm_f32_general.argtypes = [ci, ci, i64, i64, i64, cf, vp, i64, vp, i64, cf, vp, i64, vp]
+    lib.gemm_f32_general.restype = ci
+    lib.gemm_f32_general_ex.argtypes = [ci, ci, i64, i64, i64, cf, vp, i64, vp, i64, cf, vp, i64, vp, ci]
+    lib.gemm_f32_general_ex.restype = ci
     _lib = lib
     return lib
 
@@ -151,6 +160,40 @@ def gemm_f32_variant_name(variant: int):
 
 def gemm_f32_choose_variant(M, N, K, num_cu=256) -> int:
     return int(load().gemm_f32_choose_variant(M, N, K, int(num_cu)))
+
+
+# ---- C <- alpha * op(A) op(B) + beta * C ---------------------------------------------------------
+
+def gemm_f64_general(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=None):
+    """Enqueue C <- alpha * op(A) @ op(B) + beta * C (double; A is K x M when transa, B is N x K when transb)."""
+    _check(load().gemm_f64_general(int(transa), int(transb), M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                   _ptr(C), ldc, _stream(stream)))
+
+
+def gemm_f64_general_ex(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=None, variant=-1):
+    _check(load().gemm_f64_general_ex(int(transa), int(transb), M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                      _ptr(C), ldc, _stream(stream), int(variant)))
+
+
+def gemm_f64_general_raw(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=0, variant=-1) -> int:
+    return int(load().gemm_f64_general_ex(int(transa), int(transb), M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                          _ptr(C), ldc, stream, int(variant)))
+
+
+def gemm_f32_general(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=None):
+    """The float counterpart of gemm_f64_general."""
+    _check(load().gemm_f32_general(int(transa), int(transb), M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                   _ptr(C), ldc, _stream(stream)))
+
+
+def gemm_f32_general_ex(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=None, variant=-1):
+    _check(load().gemm_f32_general_ex(int(transa), int(transb), M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                      _ptr(C), ldc, _stream(stream), int(variant)))
+
+
+def gemm_f32_general_raw(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=0, variant=-1) -> int:
+    return int(load().gemm_f32_general_ex(int(transa), int(transb), M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                          _ptr(C), ldc, stream, int(variant)))
 
 
 def variant_index(name: str) -> int:

@@ -31,14 +31,28 @@ extern "C" int gemm_f32_choose_variant(int64_t M, int64_t N, int64_t K, int num_
     return choose_variant(kVariants, kNumVariants, M, N, num_cu);
 }
 
-extern "C" int gemm_f32_ex(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
-                           float *C, int64_t ldc, void *stream, int variant)
+extern "C" int gemm_f32_ex(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+                           int64_t ldb, float *C, int64_t ldc, void *stream, int variant)
 {
-    return gemm_ex<float>(kVariants, kNumVariants, M, N, K, A, lda, B, ldb, C, ldc, stream, variant);
+    return gemm_ex<float>(kVariants, kNumVariants, 0, 0, M, N, K, 1, A, lda, B, ldb, 1, C, ldc, stream, variant);
 }
 
 extern "C" int gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
                         float *C, int64_t ldc, void *stream)
 {
     return gemm_f32_ex(M, N, K, A, lda, B, ldb, C, ldc, stream, -1);
+}
+
+extern "C" int gemm_f32_general_ex(int transa, int transb, int64_t M, int64_t N, int64_t K, float alpha, const float *A,
+                                   int64_t lda, const float *B, int64_t ldb, float beta, float *C, int64_t ldc,
+                                   void *stream, int variant)
+{
+    return gemm_ex<float>(kVariants, kNumVariants, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream,
+                       variant);
+}
+
+extern "C" int gemm_f32_general(int transa, int transb, int64_t M, int64_t N, int64_t K, float alpha, const float *A,
+                                int64_t lda, const float *B, int64_t ldb, float beta, float *C, int64_t ldc, void *stream)
+{
+    return gemm_f32_general_ex(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, -1);
 }

@@ -43,9 +43,9 @@ extern "C" const char *gemm_f64_strerror(int code)
 {
     switch (code) {
     case GEMM_F64_OK: return "success";
-    case GEMM_F64_ERR_DIM: return "negative dimension or index out of range";
-    case GEMM_F64_ERR_LDA: return "lda smaller than max(1, K)";
-    case GEMM_F64_ERR_LDB: return "ldb smaller than max(1, N)";
+    case GEMM_F64_ERR_DIM: return "negative dimension, transpose flag other than 0 or 1, or index out of range";
+    case GEMM_F64_ERR_LDA: return "lda smaller than the stored row of A";
+    case GEMM_F64_ERR_LDB: return "ldb smaller than the stored row of B";
     case GEMM_F64_ERR_LDC: return "ldc smaller than max(1, N)";
     case GEMM_F64_ERR_NULL: return "null pointer for a non-empty operand";
     case GEMM_F64_ERR_ALIGN: return "pointer not aligned to the element size";
@@ -56,16 +56,30 @@ extern "C" const char *gemm_f64_strerror(int code)
     }
 }
 
-extern "C" int gemm_f64_version(void) { return 200; }
+extern "C" int gemm_f64_version(void) { return 300; }
 
 extern "C" int gemm_f64_ex(int64_t M, int64_t N, int64_t K, const double *A, int64_t lda, const double *B,
                            int64_t ldb, double *C, int64_t ldc, void *stream, int variant)
 {
-    return gemm_ex<double>(kVariants, kNumVariants, M, N, K, A, lda, B, ldb, C, ldc, stream, variant);
+    return gemm_ex<double>(kVariants, kNumVariants, 0, 0, M, N, K, 1, A, lda, B, ldb, 1, C, ldc, stream, variant);
 }
 
 extern "C" int gemm_f64(int64_t M, int64_t N, int64_t K, const double *A, int64_t lda, const double *B, int64_t ldb,
                         double *C, int64_t ldc, void *stream)
 {
     return gemm_f64_ex(M, N, K, A, lda, B, ldb, C, ldc, stream, -1);
+}
+
+extern "C" int gemm_f64_general_ex(int transa, int transb, int64_t M, int64_t N, int64_t K, double alpha, const double *A,
+                                   int64_t lda, const double *B, int64_t ldb, double beta, double *C, int64_t ldc,
+                                   void *stream, int variant)
+{
+    return gemm_ex<double>(kVariants, kNumVariants, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream,
+                       variant);
+}
+
+extern "C" int gemm_f64_general(int transa, int transb, int64_t M, int64_t N, int64_t K, double alpha, const double *A,
+                                int64_t lda, const double *B, int64_t ldb, double beta, double *C, int64_t ldc, void *stream)
+{
+    return gemm_f64_general_ex(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, -1);
 }

@@ -46,17 +46,22 @@ inline int choose_variant(const Variant *variants, int count, int64_t M, int64_t
     return best;
 }
 
+// Stored shapes: A is M x K (K x M when transa), B is K x N (N x K when transb), C is M x N; a leading
+// dimension must cover the stored row.  A and B are only required when the product is formed
+// (ab_read: alpha != 0 and K > 0).
 template <typename T>
-int validate(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B, int64_t ldb, const T *C,
-             int64_t ldc)
+int validate(int transa, int transb, int64_t M, int64_t N, int64_t K, bool ab_read, const T *A, int64_t lda, const T *B,
+             int64_t ldb, const T *C, int64_t ldc)
 {
     if (M < 0 || N < 0 || K < 0) return GEMM_F64_ERR_DIM;
+    if ((transa != 0 && transa != 1) || (transb != 0 && transb != 1)) return GEMM_F64_ERR_DIM;
     if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
-    if (lda < (K > 1 ? K : 1)) return GEMM_F64_ERR_LDA;
-    if (ldb < (N > 1 ? N : 1)) return GEMM_F64_ERR_LDB;
+    const int64_t a_width = transa ? M : K, b_width = transb ? K : N;
+    if (lda < (a_width > 1 ? a_width : 1)) return GEMM_F64_ERR_LDA;
+    if (ldb < (b_width > 1 ? b_width : 1)) return GEMM_F64_ERR_LDB;
     if (ldc < (N > 1 ? N : 1)) return GEMM_F64_ERR_LDC;
     const bool c_live = M > 0 && N > 0;
-    const bool ab_live = c_live && K > 0;
+    const bool ab_live = c_live && K > 0 && ab_read;
     if (c_live && C == nullptr) return GEMM_F64_ERR_NULL;
     if (ab_live && (A == nullptr || B == nullptr)) return GEMM_F64_ERR_NULL;
     const uintptr_t mask = sizeof(T) - 1;
@@ -66,8 +71,8 @@ int validate(int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *
 }
 
 // 16-byte global->LDS copies need 16-byte aligned bases and leading dimensions that are multiples of
-// the elements per 16 bytes; their per-lane byte offsets (up to 128 rows of A, a few rows of B) are
-// 32-bit, which bounds the leading dimensions.
+// the elements per 16 bytes; their per-lane byte offsets (up to 128 stored rows) are 32-bit, which
+// bounds the leading dimensions.
 template <typename T>
 bool async_copies_possible(const T *A, int64_t lda, const T *B, int64_t ldb)
 {
@@ -76,9 +81,9 @@ bool async_copies_possible(const T *A, int64_t lda, const T *B, int64_t ldb)
            ldb < (1 << 20);
 }
 
-template <typename T, int BM, int BN, int WM, int WN>
-hipError_t launch_mfma(int M, int N, int K, const T *A, int64_t lda, const T *B, int64_t ldb, T *C, int64_t ldc,
-                       hipStream_t stream)
+template <typename T, int BM, int BN, int WM, int WN, bool TA, bool TB>
+hipError_t launch_mfma_t(int M, int N, int K, T alpha, const T *A, int64_t lda, const T *B, int64_t ldb, T beta, T *C,
+                         int64_t ldc, hipStream_t stream)
 {
     constexpr int BK = 8 * (16 / (int)sizeof(T));
     const int tiles_m = (int)ceil_div(M, BM), tiles_n = (int)ceil_div(N, BN);
@@ -87,24 +92,47 @@ hipError_t launch_mfma(int M, int N, int K, const T *A, int64_t lda, const T *B,
     // The lean kernel assumes full tiles everywhere, whole K stages and aligned operands.
     const bool lean = vec && (M % BM == 0) && (N % BN == 0) && (K % BK == 0);
     if (lean)
-        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kLean>), grid, block, 0, stream, M, N, K, A, lda, B,
-                           ldb, C, ldc, tiles_m, tiles_n);
+        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kLean, TA, TB>), grid, block, 0, stream, M, N, K, alpha, A,
+                           lda, B, ldb, beta, C, ldc, tiles_m, tiles_n);
     else if (vec)
-        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kGeneric>), grid, block, 0, stream, M, N, K, A, lda, B,
-                           ldb, C, ldc, tiles_m, tiles_n);
+        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kGeneric, TA, TB>), grid, block, 0, stream, M, N, K, alpha,
+                           A, lda, B, ldb, beta, C, ldc, tiles_m, tiles_n);
     else
-        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kStaged>), grid, block, 0, stream, M, N, K, A, lda, B,
-                           ldb, C, ldc, tiles_m, tiles_n);
+        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kStaged, TA, TB>), grid, block, 0, stream, M, N, K, alpha,
+                           A, lda, B, ldb, beta, C, ldc, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+template <typename T, int BM, int BN, int WM, int WN>
+hipError_t launch_mfma(int transa, int transb, int M, int N, int K, T alpha, const T *A, int64_t lda, const T *B,
+                       int64_t ldb, T beta, T *C, int64_t ldc, hipStream_t stream)
+{
+    if (!transa && !transb)
+        return launch_mfma_t<T, BM, BN, WM, WN, false, false>(M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+    if (!transa && transb)
+        return launch_mfma_t<T, BM, BN, WM, WN, false, true>(M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+    if (transa && !transb)
+        return launch_mfma_t<T, BM, BN, WM, WN, true, false>(M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+    return launch_mfma_t<T, BM, BN, WM, WN, true, true>(M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+}
+
+template <typename T>
+hipError_t launch_naive(int transa, int transb, int M, int N, int K, T alpha, const T *A, int64_t lda, const T *B,
+                        int64_t ldb, T beta, T *C, int64_t ldc, hipStream_t stream)
+{
+    const int64_t total = (int64_t)M * N;
+    const dim3 grid((unsigned)ceil_div(total, 256)), block(256);
+    hipLaunchKernelGGL(gemm_naive_kernel<T>, grid, block, 0, stream, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta,
+                       C, ldc);
     return hipGetLastError();
 }
 
 template <typename T>
-hipError_t launch_naive(int M, int N, int K, const T *A, int64_t lda, const T *B, int64_t ldb, T *C, int64_t ldc,
-                        hipStream_t stream)
+hipError_t launch_scale(int M, int N, T beta, T *C, int64_t ldc, hipStream_t stream)
 {
     const int64_t total = (int64_t)M * N;
     const dim3 grid((unsigned)ceil_div(total, 256)), block(256);
-    hipLaunchKernelGGL(gemm_naive_kernel<T>, grid, block, 0, stream, M, N, K, A, lda, B, ldb, C, ldc);
+    hipLaunchKernelGGL(scale_c_kernel<T>, grid, block, 0, stream, M, N, beta, C, ldc);
     return hipGetLastError();
 }
 
@@ -117,28 +145,34 @@ inline int current_cu_count()
     return 256;
 }
 
-// The body common to gemm_f64_ex and gemm_f32_ex.
+// The body common to all entry points: C <- alpha * op(A) op(B) + beta * C.
+//   alpha == 0 or K == 0: A and B are not read; C is scaled by beta (untouched when beta == 1).
+//   beta == 0: C is not read.
 template <typename T>
-int gemm_ex(const Variant *variants, int count, int64_t M, int64_t N, int64_t K, const T *A, int64_t lda, const T *B,
-            int64_t ldb, T *C, int64_t ldc, void *stream_, int variant)
+int gemm_ex(const Variant *variants, int count, int transa, int transb, int64_t M, int64_t N, int64_t K, T alpha,
+            const T *A, int64_t lda, const T *B, int64_t ldb, T beta, T *C, int64_t ldc, void *stream_, int variant)
 {
-    const int rc = validate(M, N, K, A, lda, B, ldb, C, ldc);
+    const bool product = (alpha != T(0)) && K != 0;
+    const int rc = validate(transa, transb, M, N, K, product, A, lda, B, ldb, C, ldc);
     if (rc != GEMM_F64_OK) return rc;
     if (variant < -1 || variant >= count) return GEMM_F64_ERR_VARIANT;
-    if (M == 0 || N == 0 || K == 0) return GEMM_F64_OK;
+    if (M == 0 || N == 0) return GEMM_F64_OK;
+    if (ceil_div(M * N, 256) > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
     hipStream_t stream = (hipStream_t)stream_;
-    if (variant == -1) variant = choose_variant(variants, count, M, N, current_cu_count());
     const int m = (int)M, n = (int)N, k = (int)K;
     hipError_t err = hipSuccess;
+    if (!product) {
+        if (beta == T(1)) return GEMM_F64_OK;
+        err = launch_scale<T>(m, n, beta, C, ldc, stream);
+        return err == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
+    }
+    if (variant == -1) variant = choose_variant(variants, count, M, N, current_cu_count());
     switch (variant) {
-    case 0:
-        if (ceil_div(M * N, 256) > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
-        err = launch_naive<T>(m, n, k, A, lda, B, ldb, C, ldc, stream);
-        break;
-    case 1: err = launch_mfma<T, 128, 128, 2, 2>(m, n, k, A, lda, B, ldb, C, ldc, stream); break;
-    case 2: err = launch_mfma<T, 64, 64, 2, 2>(m, n, k, A, lda, B, ldb, C, ldc, stream); break;
-    case 3: err = launch_mfma<T, 128, 64, 2, 2>(m, n, k, A, lda, B, ldb, C, ldc, stream); break;
-    case 4: err = launch_mfma<T, 64, 128, 2, 2>(m, n, k, A, lda, B, ldb, C, ldc, stream); break;
+    case 0: err = launch_naive<T>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
+    case 1: err = launch_mfma<T, 128, 128, 2, 2>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
+    case 2: err = launch_mfma<T, 64, 64, 2, 2>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
+    case 3: err = launch_mfma<T, 128, 64, 2, 2>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
+    case 4: err = launch_mfma<T, 64, 128, 2, 2>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
     default: return GEMM_F64_ERR_VARIANT;
     }
     return err == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;

@@ -119,33 +119,228 @@ __device__ __forceinline__ void async_copy4(uint32_t voff, const void *sbase, ui
                  : "memory");
 }
 
-// One workgroup = 256 threads = 4 waves arranged WM x WN; each wave owns a (BM/WM) x (BN/WN)
-// patch of the macro-tile as MI x NI accumulator tiles of 16 x 16.
+// The scalar tail of C <- alpha * s + beta * c: t = alpha * s, then t itself when beta is zero (c is
+// not used), else t + beta * c, every operation rounded on its own (no fused multiply-add), so that
+// the tail is the same sequence of roundings as a term-by-term evaluation; with alpha = beta = 1 both
+// products are exact and what is left is the single rounding of s + c.
+template <typename T>
+__device__ __forceinline__ T scaled_update(T alpha, T s, T beta, T c, bool read_c)
+{
+#pragma clang fp contract(off)
+    const T t = alpha * s;
+    if (!read_c) return t;
+    const T u = beta * c;
+    return t + u;
+}
+
+// One operand panel of the macro-tile: how a BX x BK slice (BX = BM rows of op(A), or BN columns of
+// op(B)) is fetched from memory, laid out in LDS and read back as MFMA operand fragments.  The two MFMA
+// operands are symmetric (lane l supplies element (x = l % 16, k = l / 16) of either), so what matters is
+// only which index is contiguous in memory:
 //
-// LDS layout of one stage (BK = 8 * E values of k), chosen so that every access is contiguous:
-//   A: 1 KiB chunks indexed [i / 16][h], h = kc / 4 with kc = k / E the cell index along k; inside a
-//      chunk the 16-byte cell of lane-slot (kq, ii), kq = kc % 4, ii = i % 16, sits at
-//      (kq * 16 + ii) * 16 and holds A[i][E*kc .. E*kc + E-1].  A wave's MFMA operand fetch for one
-//      16-row block and one h is then a single 1 KiB lane-linear ds_read_b128, and its E elements
-//      feed E MFMA k-steps: step e uses k = E * (4h + l/16) + e in lane group l/16.
-//   B: groups of E rows [k / E] at a stride of E*BN*sizeof(T) + 16*sizeof(T) bytes, the rows of a
-//      group BN*sizeof(T) apart; a lane reads B[E*(4h + l/16) + e][j] for e = 0..E-1.  The group
-//      stride is 16*sizeof(T) modulo 256 bytes, so the 16-lane groups that are served together
-//      fall into different banks.
+//   KMAJOR (k contiguous: A as given, or a transposed B stored N x K): element (x, k) at P[x * ld + k].
+//      LDS: 1 KiB chunks indexed [x / 16][h], h = kc / 4 with kc = k / E the cell index along k; inside a
+//      chunk the 16-byte cell of lane-slot (kq, xx), kq = kc % 4, xx = x % 16, sits at (kq * 16 + xx) * 16
+//      and holds E consecutive k.  A wave's operand fetch for one 16-wide block and one h is a single
+//      1 KiB lane-linear ds_read_b128, and its E elements feed E MFMA k-steps: step e uses
+//      k = E * (4h + l/16) + e in lane group l/16.
+//   not KMAJOR (x contiguous: B as given, or a transposed A stored K x M): element (x, k) at P[k * ld + x].
+//      LDS: groups of E rows [k / E] at a stride of E*BX*sizeof(T) + 16*sizeof(T) bytes, the rows of a
+//      group BX*sizeof(T) apart; a lane reads rows E*(4h + l/16) + e, e = 0..E-1, at its own x: the same
+//      k per step as above.  The group stride is 16*sizeof(T) modulo 256 bytes, so the 16-lane groups
+//      that are served together fall into different banks.
+//
 // Both layouts are exactly what a 16-byte-per-lane global->LDS load writes (lane-linear 1 KiB), so
-// full tiles are staged with global_load_lds_dwordx4 and never pass through VGPRs.
+// full panels are staged with global_load_lds_dwordx4 and never pass through VGPRs.  Every address of
+// that path is a wave-uniform 64-bit base, advanced with scalar arithmetic, plus a 32-bit per-lane
+// byte offset computed once: MFMAs and ordinary vector ALU instructions compete for the same issue
+// cycles on this chip, so the K loop should contain none of the latter.  (The host only selects the
+// path when 128 * ld, in bytes, fits in 31 bits.)
+//
+// Edges along x (GENERIC only).  KMAJOR: rows at or beyond the extent X are redirected to row X - 1;
+// they only feed outputs that are never stored, so no zero fill is needed and such tiles stay on the
+// asynchronous path.  Not KMAJOR: lanes whose cell of E columns lies outside are switched off (their
+// LDS cells keep stale bits, which again only feed outputs never stored) and a partly valid last cell
+// is fetched on its own, four bytes per lane.
+//
+// The VGPR path (load_regs / store_regs: ragged last K stage, unaligned operands) loads element-wise,
+// with zeros outside the logical matrix, and writes the same LDS layout.  Both operands are zeroed for
+// k >= K, so padding only ever forms 0 * 0.
+template <typename T, bool KMAJOR, int BX, bool GENERIC>
+struct Panel {
+    typedef Elem<T> EL;
+    typedef typename EL::cell_t cell_t;
+    static constexpr int E = EL::E;
+    static constexpr int SZ = (int)sizeof(T);
+    static constexpr int BK = 8 * E;
+    static_assert(BX == 64 || BX == 128, "supported panel widths");
+    // KMAJOR
+    static constexpr int CHUNKS = (BX / 16) * 2;
+    static constexpr int CHUNKS_PER_WAVE = CHUNKS / 4;
+    // not KMAJOR
+    static constexpr int ROW = BX * SZ;                // bytes between consecutive k rows of a group
+    static constexpr int GROUP = E * ROW + 16 * SZ;    // bytes between groups of E rows
+    static_assert(GROUP % 256 == 16 * SZ, "group stride must be 16 elements modulo 256 bytes");
+    static constexpr int LOADS = (BK * BX * SZ) / 1024;  // 1 KiB global->LDS loads per stage
+    static constexpr int LOADS_PER_WAVE = LOADS / 4;
+    static constexpr int RPI = 1024 / ROW;             // k rows covered by one such load
+    static constexpr int LPR = 64 / RPI;               // lanes per row in it
+    static_assert(RPI >= 1 && RPI <= E && E % RPI == 0, "a load stays inside one group of rows");
+    static constexpr int Q_GROUPS = (4 * RPI) / E;
+    static_assert((4 * RPI) % E == 0, "loads of one wave are whole groups apart");
+    static constexpr int CPR = BX / E;                 // cells per k row
+    static_assert(64 % CPR == 0, "a wave covers whole rows of cells");
+
+    static constexpr int STAGE_BYTES = KMAJOR ? CHUNKS * 1024 : 8 * GROUP;
+    static constexpr int NR = BX / 32;                 // 16-byte cells per thread per stage on the VGPR path
+
+    const T *P;
+    int64_t ld;
+    int x0, X, K;
+    int w, l, lg, li;
+    uint32_t voff[KMAJOR ? CHUNKS_PER_WAVE : 1];
+    const char *base;
+    bool edge;
+
+    __device__ __forceinline__ void init(const T *P_, int64_t ld_, int x0_, int X_, int K_, int w_, int l_)
+    {
+        P = P_; ld = ld_; x0 = x0_; X = X_; K = K_; w = w_; l = l_;
+        lg = l >> 4; li = l & 15;
+        edge = GENERIC && (x0 + BX > X);
+        if constexpr (KMAJOR) {
+            // chunk c = (blk, h): lane l fetches the cell (row blk*16 + l%16, cell 4h + l/16 along k)
+#pragma unroll
+            for (int q = 0; q < CHUNKS_PER_WAVE; ++q) {
+                const int c = w + 4 * q;
+                const int blk = c >> 1, h = c & 1;
+                int row = blk * 16 + li;
+                if (GENERIC) row = (x0 + row < X) ? row : (X - 1 - x0);
+                voff[q] = (uint32_t)(((int64_t)row * ld + E * (4 * h + lg)) * SZ);
+            }
+            base = reinterpret_cast<const char *>(P + (int64_t)x0 * ld);
+        } else {
+            // load r covers k rows r*RPI .. r*RPI + RPI-1: lane l fetches row r*RPI + l/LPR, cell l%LPR
+            voff[0] = (uint32_t)((((int64_t)(l / LPR)) * ld + E * (l % LPR)) * SZ);
+            base = reinterpret_cast<const char *>(P + x0);
+        }
+    }
+
+    // each wave issues its share of the 1 KiB global->LDS loads of stage kt; `dst` is the LDS byte
+    // address of this panel in the destination stage buffer
+    __device__ __forceinline__ void fetch_async(int kt, uint32_t dst) const
+    {
+        if constexpr (KMAJOR) {
+            const char *src = base + (int64_t)kt * (BK * SZ);
+#pragma unroll
+            for (int q = 0; q < CHUNKS_PER_WAVE; ++q) async_copy16(voff[q], src, dst + w * 1024 + q * 4096);
+        } else {
+            // load r = w + 4q starts at k row r * RPI = w * RPI + q * (4 * RPI); 4 * RPI is a multiple
+            // of E, so q only moves the destination by whole groups
+            const int64_t row_bytes = ld * SZ;
+            const uint32_t dst0 = dst + ((w * RPI) / E) * GROUP + ((w * RPI) % E) * ROW;
+            const char *src0 = base + (int64_t)(kt * BK + w * RPI) * row_bytes;
+            if (!edge) {
+#pragma unroll
+                for (int q = 0; q < LOADS_PER_WAVE; ++q)
+                    async_copy16(voff[0], src0 + (int64_t)(4 * RPI * q) * row_bytes, dst0 + q * Q_GROUPS * GROUP);
+            } else {
+                const int valid = X - x0;                      // 1 .. BX-1 columns of this panel exist
+                const bool cell_ok = E * (l % LPR) + E <= valid;
+                const int xt = (valid / E) * E;                // first column of a partly valid cell
+                const int tail_dwords = (valid % E) * (SZ / 4);
+#pragma unroll
+                for (int q = 0; q < LOADS_PER_WAVE; ++q) {
+                    const char *src = src0 + (int64_t)(4 * RPI * q) * row_bytes;
+                    const uint32_t d = dst0 + q * Q_GROUPS * GROUP;
+                    if (cell_ok) async_copy16(voff[0], src, d);
+                    if (l < tail_dwords) {
+#pragma unroll
+                        for (int rr = 0; rr < RPI; ++rr)
+                            async_copy4(4 * l, src + rr * row_bytes + xt * SZ, d + rr * ROW + xt * SZ);
+                    }
+                }
+            }
+        }
+    }
+
+    __device__ __forceinline__ void load_regs(int kt, T (&r)[E * NR]) const
+    {
+        const int k0 = kt * BK;
+#pragma unroll
+        for (int q = 0; q < NR; ++q) {
+            if constexpr (KMAJOR) {
+                const int row = x0 + li + 16 * w + 64 * (q >> 1), k = k0 + E * (lg + 4 * (q & 1));
+                const T *p = P + (int64_t)row * ld + k;
+#pragma unroll
+                for (int e = 0; e < E; ++e) r[E * q + e] = (row < X && k + e < K) ? p[e] : T(0);
+            } else {
+                const int kk = k0 + l / CPR + (64 / CPR) * w + (kThreads / CPR) * q, col = x0 + E * (l % CPR);
+                const T *p = P + (int64_t)kk * ld + col;
+#pragma unroll
+                for (int e = 0; e < E; ++e) r[E * q + e] = (kk < K && col + e < X) ? p[e] : T(0);
+            }
+        }
+    }
+
+    __device__ __forceinline__ void store_regs(char *stage, const T (&r)[E * NR]) const
+    {
+#pragma unroll
+        for (int q = 0; q < NR; ++q) {
+            cell_t v;
+#pragma unroll
+            for (int e = 0; e < E; ++e) v[e] = r[E * q + e];
+            if constexpr (KMAJOR) {
+                const int i = li + 16 * w + 64 * (q >> 1), kc = lg + 4 * (q & 1);
+                *reinterpret_cast<cell_t *>(stage + (((i >> 4) << 1) | (kc >> 2)) * 1024 + (kc & 3) * 256 + (i & 15) * 16) = v;
+            } else {
+                const int kk = l / CPR + (64 / CPR) * w + (kThreads / CPR) * q, xc = l % CPR;
+                *reinterpret_cast<cell_t *>(stage + (kk / E) * GROUP + (kk % E) * ROW + xc * 16) = v;
+            }
+        }
+    }
+
+    // byte offset, inside this panel's part of a stage, of the first fragment of the wave whose patch
+    // starts at element wx_off of the panel
+    __device__ __forceinline__ int frag_base(int wx_off) const
+    {
+        if constexpr (KMAJOR) return ((wx_off / 16) << 1) * 1024 + l * 16;      // + xi*2048 + h*1024
+        else return lg * GROUP + (wx_off + li) * SZ;                            // + h*4*GROUP + xi*16*SZ + e*ROW
+    }
+
+    // fragments of one half-stage (h) = E MFMA k-steps, for XI consecutive 16-wide blocks
+    template <int XI>
+    static __device__ __forceinline__ void read_frags(const char *panel, int fbase, int h, cell_t (&f)[XI])
+    {
+#pragma unroll
+        for (int xi = 0; xi < XI; ++xi) {
+            if constexpr (KMAJOR) {
+                f[xi] = *reinterpret_cast<const cell_t *>(panel + fbase + xi * 2048 + h * 1024);
+            } else {
+                const char *p = panel + fbase + h * 4 * GROUP + xi * 16 * SZ;
+#pragma unroll
+                for (int e = 0; e < E; ++e) f[xi][e] = *reinterpret_cast<const T *>(p + e * ROW);
+            }
+        }
+    }
+};
+
+// One workgroup = 256 threads = 4 waves arranged WM x WN; each wave owns a (BM/WM) x (BN/WN)
+// patch of the macro-tile as MI x NI accumulator tiles of 16 x 16.  One LDS stage holds BK = 8 * E
+// values of k (16 for double, 32 for float) of the op(A) panel followed by the op(B) panel; see Panel
+// for the layouts.  TA / TB say that A / B is stored transposed (K x M / N x K).
 //
 // MODE = kLean: every tile is full, K is a multiple of BK, A and B are 16-byte aligned with
 // leading dimensions that are multiples of E (checked on the host); only the asynchronous path is
 // compiled in.
 // MODE = kGeneric adds the element-wise, zero-filled path through VGPRs for the ragged last K stage
-// (synchronous: once per tile) and handles edge tiles.
+// (synchronous: once per tile; zeros are required there because k >= K contributes to every output)
+// and handles edge tiles.
 // MODE = kStaged is for unaligned operands: every stage goes through VGPRs, loaded two stages ahead
 // and written to LDS one stage ahead, at the price of 16 to 32 more live registers.
-template <typename T, int BM, int BN, int WM, int WN, int MODE>
+template <typename T, int BM, int BN, int WM, int WN, int MODE, bool TA, bool TB>
 __global__ void __launch_bounds__(kThreads, 2)
-gemm_mfma_kernel(int M, int N, int K, const T *__restrict__ A, int64_t lda, const T *__restrict__ B, int64_t ldb,
-                 T *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n)
+gemm_mfma_kernel(int M, int N, int K, T alpha, const T *__restrict__ A, int64_t lda, const T *__restrict__ B,
+                 int64_t ldb, T beta, T *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n)
 {
     typedef Elem<T> EL;
     typedef typename EL::cell_t cell_t;
@@ -161,21 +356,11 @@ gemm_mfma_kernel(int M, int N, int K, const T *__restrict__ A, int64_t lda, cons
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int MI = TM / 16, NI = TN / 16;
     static_assert(MI >= 1 && NI >= 1 && TM % 16 == 0 && TN % 16 == 0, "wave tile is a grid of 16x16 tiles");
-    static_assert(BM % 64 == 0 && (BN == 64 || BN == 128), "supported macro-tiles");
-    constexpr int A_CHUNKS = (BM / 16) * 2;
-    constexpr int A_STAGE = A_CHUNKS * 1024;          // bytes
-    constexpr int B_ROW = BN * SZ;                    // bytes between consecutive k rows of a group
-    constexpr int B_GROUP = E * B_ROW + 16 * SZ;      // bytes between groups of E rows
-    static_assert(B_GROUP % 256 == 16 * SZ, "group stride must be 16 elements modulo 256 bytes");
-    constexpr int B_STAGE = 8 * B_GROUP;
-    constexpr int STAGE = A_STAGE + B_STAGE;
-    constexpr int B_LOADS = (BK * BN * SZ) / 1024;    // 1 KiB global->LDS loads per B stage
-    constexpr int RPI = 1024 / B_ROW;                 // B rows covered by one such load
-    constexpr int LPR = 64 / RPI;                     // lanes per row in it
-    static_assert(RPI >= 1 && RPI <= E && E % RPI == 0, "a load stays inside one group of rows");
-    constexpr int NA = BM / 32, NB = BN / 32;         // 16-byte cells per thread per stage (VGPR path)
-    constexpr int CPR = BN / E;                       // cells per B row
-    static_assert(64 % CPR == 0, "a wave covers whole B rows of cells");
+    typedef Panel<T, !TA, BM, GENERIC> PA;
+    typedef Panel<T, TB, BN, GENERIC> PB;
+    constexpr int A_STAGE = PA::STAGE_BYTES;
+    constexpr int STAGE = A_STAGE + PB::STAGE_BYTES;
+    constexpr int NA = PA::NR, NB = PB::NR;
 
     __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE];
 
@@ -191,127 +376,23 @@ gemm_mfma_kernel(int M, int N, int K, const T *__restrict__ A, int64_t lda, cons
 
     const bool tile_full = (m0 + BM <= M) && (n0 + BN <= N);
     const int nk = (K + BK - 1) / BK;
-    // Number of leading stages fetched by the asynchronous global->LDS path.  Rows of an A tile that
-    // lie below the matrix are redirected to row M - 1: they only feed rows of C that are never
-    // stored, so no zero fill is needed in M and such tiles stay on the fast path.  Columns of B to
-    // the right of the matrix feed only columns of C that are never stored either; there the lanes
-    // whose cell of columns lies outside are switched off (their LDS cells keep stale bits) and a
-    // partly valid last cell is fetched on its own, four bytes per lane.  Only the ragged last K
-    // stage goes through VGPRs, for both operands, because there zeros are required: k >= K
-    // contributes to every output.
+    // number of leading stages fetched by the asynchronous global->LDS path; only the ragged last K
+    // stage goes through VGPRs, for both operands
     const int nk_async = STAGED ? 0 : GENERIC ? K / BK : nk;
-    const bool b_edge = GENERIC && (n0 + BN > N);
 
-    // ---- asynchronous path: each wave issues its share of 1 KiB global->LDS loads -------------
-    // A chunk c = (iblk, h): lane l fetches the cell (row iblk*16 + l%16, cell 4h + l/16 along k).
-    // B load r covers rows r*RPI .. r*RPI + RPI-1: lane l fetches row r*RPI + l/LPR, cell l%LPR.
-    // Every address is a wave-uniform 64-bit base, advanced with scalar arithmetic, plus a 32-bit
-    // per-lane byte offset computed once: MFMAs and ordinary vector ALU instructions compete for
-    // the same issue cycles on this chip, so the K loop should contain none of the latter.
-    // (The host only selects this path when BM * lda and E * ldb, in bytes, fit in 31 bits.)
-    constexpr int A_PER_WAVE = A_CHUNKS / 4, B_PER_WAVE = B_LOADS / 4;
+    PA pa;
+    PB pb;
+    pa.init(A, lda, m0, M, K, w, l);
+    pb.init(B, ldb, n0, N, K, w, l);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
-    uint32_t a_voff[A_PER_WAVE];
-#pragma unroll
-    for (int q = 0; q < A_PER_WAVE; ++q) {
-        const int c = w + 4 * q;
-        const int iblk = c >> 1, h = c & 1;
-        int row = iblk * 16 + li;
-        if (GENERIC) row = (m0 + row < M) ? row : (M - 1 - m0);
-        a_voff[q] = (uint32_t)(((int64_t)row * lda + E * (4 * h + lg)) * SZ);
-    }
-    const uint32_t b_voff = (uint32_t)((((int64_t)(l / LPR)) * ldb + E * (l % LPR)) * SZ);
-    const char *const a_base = reinterpret_cast<const char *>(A + (int64_t)m0 * lda);
-    const char *const b_base = reinterpret_cast<const char *>(B + n0);
-    auto fetch_async_a = [&](int kt, int buf) {
-        const uint32_t dst = lds_base + buf * STAGE + w * 1024;
-        const char *src = a_base + (int64_t)kt * (BK * SZ);
-#pragma unroll
-        for (int q = 0; q < A_PER_WAVE; ++q) async_copy16(a_voff[q], src, dst + q * 4096);
-    };
-    auto fetch_async_b = [&](int kt, int buf) {
-        // load r = w + 4q starts at row r * RPI = w * RPI + q * (4 * RPI); 4 * RPI is a multiple of E,
-        // so q only moves the destination by whole groups
-        const int64_t row_bytes = ldb * SZ;
-        const uint32_t dst0 = lds_base + buf * STAGE + A_STAGE + ((w * RPI) / E) * B_GROUP + ((w * RPI) % E) * B_ROW;
-        const char *src0 = b_base + (int64_t)(kt * BK + w * RPI) * row_bytes;
-        constexpr int Q_GROUPS = (4 * RPI) / E;
-        static_assert((4 * RPI) % E == 0, "loads of one wave are whole groups apart");
-        if (!b_edge) {
-#pragma unroll
-            for (int q = 0; q < B_PER_WAVE; ++q)
-                async_copy16(b_voff, src0 + (int64_t)(4 * RPI * q) * row_bytes, dst0 + q * Q_GROUPS * B_GROUP);
-        } else {
-            const int valid = N - n0;                      // 1 .. BN-1 columns of this tile exist
-            const bool cell_ok = E * (l % LPR) + E <= valid;
-            const int jt = (valid / E) * E;                // first column of a partly valid cell
-            const int tail_dwords = (valid % E) * (SZ / 4);
-#pragma unroll
-            for (int q = 0; q < B_PER_WAVE; ++q) {
-                const char *src = src0 + (int64_t)(4 * RPI * q) * row_bytes;
-                const uint32_t dst = dst0 + q * Q_GROUPS * B_GROUP;
-                if (cell_ok) async_copy16(b_voff, src, dst);
-                if (l < tail_dwords) {
-#pragma unroll
-                    for (int rr = 0; rr < RPI; ++rr)
-                        async_copy4(4 * l, src + rr * row_bytes + jt * SZ, dst + rr * B_ROW + jt * SZ);
-                }
-            }
-        }
-    };
 
-    // ---- VGPR path (ragged K, unaligned operands): element-wise loads, zero outside the logical
-    // matrices, written to LDS in the same layout.  Both operands are zeroed for k >= K, so padding
-    // only ever forms 0 * 0.
-    auto load_regs_a = [&](int kt, T (&ra)[E * NA]) {
-        const int k0 = kt * BK;
-#pragma unroll
-        for (int q = 0; q < NA; ++q) {
-            const int row = m0 + li + 16 * w + 64 * (q >> 1), k = k0 + E * (lg + 4 * (q & 1));
-            const T *p = A + (int64_t)row * lda + k;
-#pragma unroll
-            for (int e = 0; e < E; ++e) ra[E * q + e] = (row < M && k + e < K) ? p[e] : T(0);
-        }
-    };
-    auto store_regs_a = [&](int buf, const T (&ra)[E * NA]) {
-        char *stage = lds + buf * STAGE;
-#pragma unroll
-        for (int q = 0; q < NA; ++q) {
-            const int i = li + 16 * w + 64 * (q >> 1), kc = lg + 4 * (q & 1);
-            cell_t v;
-#pragma unroll
-            for (int e = 0; e < E; ++e) v[e] = ra[E * q + e];
-            *reinterpret_cast<cell_t *>(stage + (((i >> 4) << 1) | (kc >> 2)) * 1024 + (kc & 3) * 256 + (i & 15) * 16) = v;
-        }
-    };
-    auto load_regs_b = [&](int kt, T (&rb)[E * NB]) {
-        const int k0 = kt * BK;
-#pragma unroll
-        for (int q = 0; q < NB; ++q) {
-            const int kk = k0 + l / CPR + (64 / CPR) * w + (kThreads / CPR) * q, col = n0 + E * (l % CPR);
-            const T *p = B + (int64_t)kk * ldb + col;
-#pragma unroll
-            for (int e = 0; e < E; ++e) rb[E * q + e] = (kk < K && col + e < N) ? p[e] : T(0);
-        }
-    };
-    auto store_regs_b = [&](int buf, const T (&rb)[E * NB]) {
-        char *stage = lds + buf * STAGE;
-#pragma unroll
-        for (int q = 0; q < NB; ++q) {
-            const int kk = l / CPR + (64 / CPR) * w + (kThreads / CPR) * q, jc = l % CPR;
-            cell_t v;
-#pragma unroll
-            for (int e = 0; e < E; ++e) v[e] = rb[E * q + e];
-            *reinterpret_cast<cell_t *>(stage + A_STAGE + (kk / E) * B_GROUP + (kk % E) * B_ROW + jc * 16) = v;
-        }
-    };
     auto fetch_sync = [&](int kt, int buf) {
         T ra[E * NA];
-        load_regs_a(kt, ra);
-        store_regs_a(buf, ra);
+        pa.load_regs(kt, ra);
+        pa.store_regs(lds + buf * STAGE, ra);
         T rb[E * NB];
-        load_regs_b(kt, rb);
-        store_regs_b(buf, rb);
+        pb.load_regs(kt, rb);
+        pb.store_regs(lds + buf * STAGE + A_STAGE, rb);
     };
     // kStaged: the registers that carry a stage from its loads (after one barrier) to its LDS
     // writes (before the next)
@@ -321,8 +402,8 @@ gemm_mfma_kernel(int M, int N, int K, const T *__restrict__ A, int64_t lda, cons
     // issue what can be fetched asynchronously for stage kt (as early as its buffer is free) ...
     auto fetch_early = [&](int kt, int buf) {
         if (kt < nk_async) {
-            fetch_async_a(kt, buf);
-            fetch_async_b(kt, buf);
+            pa.fetch_async(kt, lds_base + buf * STAGE);
+            pb.fetch_async(kt, lds_base + buf * STAGE + A_STAGE);
         }
     };
     // ... and fetch the rest synchronously just before the barrier that publishes the stage
@@ -331,19 +412,12 @@ gemm_mfma_kernel(int M, int N, int K, const T *__restrict__ A, int64_t lda, cons
     };
 
     // ---- operand fragments: one half-stage (h) = E MFMA k-steps -------------------------------
-    const int a_frag = ((wm * (TM / 16)) << 1) * 1024 + l * 16;              // + mi*2048 + h*1024
-    const int b_frag = A_STAGE + lg * B_GROUP + (wn * TN + li) * SZ;         // + h*4*B_GROUP + ni*16*SZ + e*B_ROW
+    const int a_frag = pa.frag_base(wm * TM);
+    const int b_frag = A_STAGE + pb.frag_base(wn * TN);
     auto read_frags = [&](int buf, int h, cell_t (&fa)[MI], cell_t (&fb)[NI]) {
         const char *stage = lds + buf * STAGE;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-            fa[mi] = *reinterpret_cast<const cell_t *>(stage + a_frag + mi * 2048 + h * 1024);
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-            const char *p = stage + b_frag + h * 4 * B_GROUP + ni * 16 * SZ;
-#pragma unroll
-            for (int e = 0; e < E; ++e) fb[ni][e] = *reinterpret_cast<const T *>(p + e * B_ROW);
-        }
+        PA::template read_frags<MI>(stage, a_frag, h, fa);
+        PB::template read_frags<NI>(stage, b_frag, h, fb);
     };
 
     acc_t acc[MI][NI];
@@ -392,8 +466,8 @@ gemm_mfma_kernel(int M, int N, int K, const T *__restrict__ A, int64_t lda, cons
         mfma_range(fa0, fb0, NI, HALF);
         if constexpr (STAGED) {
             if (s >= 1 && s + 1 < nk) {  // stage s + 1 was loaded during the previous iteration
-                store_regs_a(cur ^ 1, reinterpret_cast<const T(&)[E * NA]>(sa));
-                store_regs_b(cur ^ 1, reinterpret_cast<const T(&)[E * NB]>(sb));
+                pa.store_regs(lds + (cur ^ 1) * STAGE, reinterpret_cast<const T(&)[E * NA]>(sa));
+                pb.store_regs(lds + (cur ^ 1) * STAGE + A_STAGE, reinterpret_cast<const T(&)[E * NB]>(sb));
             }
         } else if (GENERIC && s >= 1 && s + 1 < nk) {
             fetch_late(s + 1, cur ^ 1);
@@ -405,8 +479,8 @@ gemm_mfma_kernel(int M, int N, int K, const T *__restrict__ A, int64_t lda, cons
         read_frags(cur ^ 1, 0, fa0, fb0);
         if constexpr (STAGED) {
             if (s + 2 < nk) {
-                load_regs_a(s + 2, reinterpret_cast<T(&)[E * NA]>(sa));
-                load_regs_b(s + 2, reinterpret_cast<T(&)[E * NB]>(sb));
+                pa.load_regs(s + 2, reinterpret_cast<T(&)[E * NA]>(sa));
+                pb.load_regs(s + 2, reinterpret_cast<T(&)[E * NB]>(sb));
             }
         } else if (s + 2 < nk) {
             fetch_early(s + 2, cur);
@@ -421,36 +495,48 @@ gemm_mfma_kernel(int M, int N, int K, const T *__restrict__ A, int64_t lda, cons
     }
     if (s < nk) iteration(s, std::integral_constant<int, 0>{});
 
-    // C is read and written exactly once per element, after the K loop.  Loads are issued in batches
+    // C <- alpha * (A B) + beta * C, C read (unless beta is zero: then it may hold anything, NaN
+    // included) and written exactly once per element, after the K loop.  With alpha = beta = 1 the
+    // update is the single rounding of acc + c (see scaled_update).  Loads are issued in batches
     // of two 16-row blocks (up to 32 per lane in flight) before the first is consumed: the epilogue
     // is latency-bound, so its duration is the number of batches times the memory latency.
     const int row_base = m0 + wm * TM;
     const int col_base = n0 + wn * TN + li;
     constexpr int MB = (MI >= 2) ? 2 : 1;
+    // UNIT: alpha = beta = 1, the paper's own operation; the update is then one addition per element
+    auto epilogue = [&](auto unit_tag) {
+        constexpr bool UNIT = decltype(unit_tag)::value;
+        const bool read_c = UNIT || beta != T(0);
 #pragma unroll
-    for (int mb = 0; mb < MI; mb += MB) {
-        T cin[MB][NI][4];
+        for (int mb = 0; mb < MI; mb += MB) {
+            T cin[MB][NI][4];
 #pragma unroll
-        for (int mi = mb; mi < mb + MB; ++mi)
+            for (int mi = mb; mi < mb + MB; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
+                for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = row_base + mi * 16 + EL::d_row(r, lg), col = col_base + ni * 16;
-                    if (!GENERIC || tile_full || (row < M && col < N)) cin[mi - mb][ni][r] = C[(int64_t)row * ldc + col];
-                    else cin[mi - mb][ni][r] = T(0);
-                }
+                    for (int r = 0; r < 4; ++r) {
+                        const int row = row_base + mi * 16 + EL::d_row(r, lg), col = col_base + ni * 16;
+                        if (read_c && (!GENERIC || tile_full || (row < M && col < N)))
+                            cin[mi - mb][ni][r] = C[(int64_t)row * ldc + col];
+                        else cin[mi - mb][ni][r] = T(0);
+                    }
 #pragma unroll
-        for (int mi = mb; mi < mb + MB; ++mi)
+            for (int mi = mb; mi < mb + MB; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
+                for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = row_base + mi * 16 + EL::d_row(r, lg), col = col_base + ni * 16;
-                    if (!GENERIC || tile_full || (row < M && col < N))
-                        C[(int64_t)row * ldc + col] = cin[mi - mb][ni][r] + acc[mi][ni][r];
-                }
-    }
+                    for (int r = 0; r < 4; ++r) {
+                        const int row = row_base + mi * 16 + EL::d_row(r, lg), col = col_base + ni * 16;
+                        if (!GENERIC || tile_full || (row < M && col < N))
+                            C[(int64_t)row * ldc + col] =
+                                UNIT ? cin[mi - mb][ni][r] + acc[mi][ni][r]
+                                     : scaled_update(alpha, acc[mi][ni][r], beta, cin[mi - mb][ni][r], read_c);
+                    }
+        }
+    };
+    if (alpha == T(1) && beta == T(1)) epilogue(std::true_type{});
+    else epilogue(std::false_type{});
 }
 
 // Reference-shaped kernel without tiling or staging: one thread per element of C, k ascending.
@@ -458,16 +544,31 @@ gemm_mfma_kernel(int M, int N, int K, const T *__restrict__ A, int64_t lda, cons
 // on-device cross-check that shares nothing with the MFMA kernel.
 template <typename T>
 __global__ void __launch_bounds__(256)
-gemm_naive_kernel(int M, int N, int K, const T *__restrict__ A, int64_t lda, const T *__restrict__ B, int64_t ldb,
-                  T *__restrict__ C, int64_t ldc)
+gemm_naive_kernel(int transa, int transb, int M, int N, int K, T alpha, const T *__restrict__ A, int64_t lda,
+                  const T *__restrict__ B, int64_t ldb, T beta, T *__restrict__ C, int64_t ldc)
 {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (int64_t)M * N) return;
     const int i = (int)(idx / N), j = (int)(idx % N);
-    T c = C[(int64_t)i * ldc + j];
-    const T *a = A + (int64_t)i * lda;
-    for (int k = 0; k < K; ++k) c += a[k] * B[(int64_t)k * ldb + j];
-    C[(int64_t)i * ldc + j] = c;
+    const int64_t a_i = transa ? 1 : lda, a_k = transa ? lda : 1, b_k = transb ? 1 : ldb, b_j = transb ? ldb : 1;
+    const T *a = A + (int64_t)i * a_i, *b = B + (int64_t)j * b_j;
+    T acc = T(0);
+    for (int k = 0; k < K; ++k) acc += a[k * a_k] * b[k * b_k];
+    const bool read_c = beta != T(0);
+    const T c = read_c ? C[(int64_t)i * ldc + j] : T(0);
+    C[(int64_t)i * ldc + j] = scaled_update(alpha, acc, beta, c, read_c);
+}
+
+// C <- beta * C (all zeros when beta is zero, whatever C held): what is left of the operation when
+// alpha is zero or K is zero.
+template <typename T>
+__global__ void __launch_bounds__(256) scale_c_kernel(int M, int N, T beta, T *__restrict__ C, int64_t ldc)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)M * N) return;
+    const int i = (int)(idx / N), j = (int)(idx % N);
+    T *p = C + (int64_t)i * ldc + j;
+    *p = (beta != T(0)) ? beta * *p : T(0);
 }
 
 }  // namespace gemm_detail

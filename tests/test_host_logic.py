@@ -25,7 +25,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(binding.LIB_PATH)
     names = declared_functions()
-    assert "gemm_f64" in names and "gemm_f64_ex" in names and "gemm_f32" in names and len(names) >= 13
+    assert "gemm_f64" in names and "gemm_f64_ex" in names and "gemm_f32" in names and len(names) >= 17
     for n in names:
         assert hasattr(lib, n), "libgemm_f64.so does not export " + n
     for n in names:
@@ -122,6 +122,31 @@ def test_single_precision_entry_points_validate_like_the_double_ones():
     assert names[0] == "naive" and all(nm.endswith("x32") for nm in names[1:])
     for (M, N, K) in [(1, 1, 1), (2048, 2048, 2048), (8192, 8192, 8192), (2088, 2049, 2047)]:
         assert 1 <= binding.gemm_f32_choose_variant(M, N, K, 256) < n
+
+
+def test_general_entry_points_validate_transposed_shapes_and_folded_operands():
+    p = 0x1000
+    for raw, off in ((binding.gemm_f64_general_raw, 4), (binding.gemm_f32_general_raw, 2)):
+        ok = lambda *a, **k: raw(*a, **k)
+        # (transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc); variant 99 is rejected after
+        # validation and before any launch, so a well-formed call shows up as -9 without a GPU
+        assert ok(0, 0, 2, 3, 4, 1.0, p, 4, p, 3, 1.0, p, 3, variant=99) == -9
+        assert ok(2, 0, 2, 3, 4, 1.0, p, 4, p, 3, 1.0, p, 3) == -1
+        assert ok(0, -1, 2, 3, 4, 1.0, p, 4, p, 3, 1.0, p, 3) == -1
+        assert ok(0, 0, 2, 3, 4, 1.0, p, 3, p, 3, 1.0, p, 3) == -2        # lda < K
+        assert ok(1, 0, 2, 3, 4, 1.0, p, 1, p, 3, 1.0, p, 3) == -2        # transposed A is K x M: lda < M
+        assert ok(1, 0, 2, 3, 4, 1.0, p, 2, p, 3, 1.0, p, 3, variant=99) == -9
+        assert ok(0, 0, 2, 3, 4, 1.0, p, 4, p, 2, 1.0, p, 3) == -3        # ldb < N
+        assert ok(0, 1, 2, 3, 4, 1.0, p, 4, p, 3, 1.0, p, 3) == -3        # transposed B is N x K: ldb < K
+        assert ok(0, 1, 2, 3, 4, 1.0, p, 4, p, 4, 1.0, p, 3, variant=99) == -9
+        assert ok(0, 0, 2, 3, 4, 1.0, p, 4, p, 3, 1.0, p, 2) == -4
+        assert ok(0, 0, 2, 3, 4, 1.0, None, 4, p, 3, 1.0, p, 3) == -5
+        assert ok(0, 0, 2, 3, 4, 1.0, p + off, 4, p, 3, 1.0, p, 3) == -6
+        # alpha == 0 or K == 0: A and B are not read and may be null; beta == 1 then launches nothing
+        assert ok(0, 0, 2, 3, 4, 0.0, None, 4, None, 3, 1.0, p, 3) == 0
+        assert ok(1, 1, 2, 3, 0, 2.0, None, 2, None, 1, 1.0, p, 3) == 0
+        assert ok(0, 0, 2, 3, 4, 0.0, None, 4, None, 3, 1.0, None, 3) == -5
+        assert ok(0, 0, 0, 3, 4, 1.0, None, 4, None, 3, 0.0, None, 3) == 0
 
 
 def test_gflops_convention_matches_the_papers_printed_numbers():
