@@ -33,9 +33,13 @@ extern "C" int gemm_f64_choose_variant(int64_t M, int64_t N, int64_t K, int num_
 extern "C" int gemm_f64_tile_of_block(int64_t block, int64_t tiles_m, int64_t tiles_n, int64_t *tile_m,
                                       int64_t *tile_n)
 {
-    if (tiles_m < 1 || tiles_n < 1 || block < 0 || block >= tiles_m * tiles_n || !tile_m || !tile_n)
+    if (tiles_m < 1 || tiles_n < 1 || tiles_m > INT32_MAX || tiles_n > INT32_MAX || tiles_m * tiles_n > INT32_MAX ||
+        block < 0 || block >= tiles_m * tiles_n || !tile_m || !tile_n)
         return GEMM_F64_ERR_DIM;
-    tile_of_block(block, tiles_m, tiles_n, *tile_m, *tile_n);
+    uint32_t tm = 0, tn = 0;
+    tile_of_block((uint32_t)block, (uint32_t)tiles_m, (uint32_t)tiles_n, tm, tn);
+    *tile_m = tm;
+    *tile_n = tn;
     return GEMM_F64_OK;
 }
 

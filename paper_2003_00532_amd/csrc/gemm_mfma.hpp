@@ -50,7 +50,7 @@ template <> struct Elem<double> {
     {
         return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
     }
-    static __device__ __forceinline__ int d_row(int r, int lg) { return 4 * r + lg; }
+    static constexpr __device__ __forceinline__ int d_row(int r, int lg) { return 4 * r + lg; }
 };
 template <> struct Elem<float> {
     static constexpr int E = 4;
@@ -60,28 +60,29 @@ template <> struct Elem<float> {
     {
         return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
     }
-    static __device__ __forceinline__ int d_row(int r, int lg) { return 4 * lg + r; }
+    static constexpr __device__ __forceinline__ int d_row(int r, int lg) { return 4 * lg + r; }
 };
 
 // Workgroup id -> tile coordinates.  Block b runs on XCD b % kXcds.  Each XCD receives a
 // contiguous run of the "grouped" tile order (kGroupM tile rows at a time, column by column
 // inside a group), so the workgroups resident on one XCD at any moment form a compact patch of C
 // and re-use each other's A and B panels in that XCD's L2.
-__host__ __device__ inline void tile_of_block(int64_t b, int64_t tiles_m, int64_t tiles_n,
-                                              int64_t &tm, int64_t &tn)
+// All quantities fit in 32 bits: the host refuses problems with more than 2^31 - 1 blocks of 256 outputs.
+__host__ __device__ inline void tile_of_block(uint32_t b, uint32_t tiles_m, uint32_t tiles_n, uint32_t &tm,
+                                              uint32_t &tn)
 {
-    const int64_t total = tiles_m * tiles_n;
-    const int64_t per = total / kXcds, rem = total % kXcds;
-    const int64_t x = b % kXcds, s = b / kXcds;
-    const int64_t start = x * per + (x < rem ? x : rem);
-    const int64_t logical = start + s;
-    const int64_t width = kGroupM * tiles_n;
-    const int64_t g = logical / width;
-    const int64_t first_m = g * kGroupM;
-    const int64_t gsz = (tiles_m - first_m) < kGroupM ? (tiles_m - first_m) : kGroupM;
-    const int64_t in_g = logical % width;
-    tm = first_m + in_g % gsz;
+    const uint32_t total = tiles_m * tiles_n;
+    const uint32_t per = total / kXcds, rem = total % kXcds;
+    const uint32_t x = b % kXcds, s = b / kXcds;
+    const uint32_t start = x * per + (x < rem ? x : rem);
+    const uint32_t logical = start + s;
+    const uint32_t width = kGroupM * tiles_n;
+    const uint32_t g = logical / width;
+    const uint32_t first_m = g * kGroupM;
+    const uint32_t gsz = (tiles_m - first_m) < (uint32_t)kGroupM ? (tiles_m - first_m) : (uint32_t)kGroupM;
+    const uint32_t in_g = logical - g * width;
     tn = in_g / gsz;
+    tm = first_m + (in_g - tn * gsz);
 }
 
 // Workgroup barrier that also publishes this wave's LDS traffic: every LDS read, LDS write and
@@ -370,9 +371,9 @@ gemm_mfma_kernel(int M, int N, int K, T alpha, const T *__restrict__ A, int64_t 
     const int wm = w / WN, wn = w % WN;
     const int lg = l >> 4, li = l & 15;
 
-    int64_t tm64, tn64;
-    tile_of_block(blockIdx.x, tiles_m, tiles_n, tm64, tn64);
-    const int m0 = (int)tm64 * BM, n0 = (int)tn64 * BN;
+    uint32_t tm_u, tn_u;
+    tile_of_block(blockIdx.x, (uint32_t)tiles_m, (uint32_t)tiles_n, tm_u, tn_u);
+    const int m0 = (int)tm_u * BM, n0 = (int)tn_u * BN;
 
     const bool tile_full = (m0 + BM <= M) && (n0 + BN <= N);
     const int nk = (K + BK - 1) / BK;
@@ -500,43 +501,69 @@ gemm_mfma_kernel(int M, int N, int K, T alpha, const T *__restrict__ A, int64_t 
     // update is the single rounding of acc + c (see scaled_update).  Loads are issued in batches
     // of two 16-row blocks (up to 32 per lane in flight) before the first is consumed: the epilogue
     // is latency-bound, so its duration is the number of batches times the memory latency.
-    const int row_base = m0 + wm * TM;
+    // Addressing: one pointer per lane to its first element, then row steps of ROW_STEP * ldc elements
+    // between the four result registers of an accumulator tile and 16 * ldc between tile rows, added up
+    // as the loops go (a 64-bit add per row instead of a multiply per element); columns of one row are
+    // a compile-time offset apart.
+    const int row_base = m0 + wm * TM + EL::d_row(0, lg);
     const int col_base = n0 + wn * TN + li;
+    constexpr int ROW_STEP = EL::d_row(1, 0) - EL::d_row(0, 0);   // 4 for double, 1 for float
+    static_assert(EL::d_row(2, 0) - EL::d_row(1, 0) == ROW_STEP && EL::d_row(3, 0) - EL::d_row(2, 0) == ROW_STEP, "");
     constexpr int MB = (MI >= 2) ? 2 : 1;
-    // UNIT: alpha = beta = 1, the paper's own operation; the update is then one addition per element
-    auto epilogue = [&](auto unit_tag) {
-        constexpr bool UNIT = decltype(unit_tag)::value;
-        const bool read_c = UNIT || beta != T(0);
+    T *const c_lane = C + (int64_t)row_base * ldc + col_base;
+    const int64_t r_step = (int64_t)ROW_STEP * ldc, mi_step = 16 * ldc;
+    // Three forms, chosen once per workgroup: alpha = beta = 1 (the paper's own operation: one addition
+    // per element), beta = 0 (C is not read) and the general one.
+    constexpr int kUnit = 0, kOverwrite = 1, kScaled = 2;
+    auto epilogue = [&](auto kind_tag) {
+        constexpr int KIND = decltype(kind_tag)::value;
+        constexpr bool UNIT = KIND == kUnit;
+        constexpr bool read_c = KIND != kOverwrite;
+        T *c_mb = c_lane;
 #pragma unroll
         for (int mb = 0; mb < MI; mb += MB) {
             T cin[MB][NI][4];
+            T *c_mi = c_mb;
 #pragma unroll
-            for (int mi = mb; mi < mb + MB; ++mi)
+            for (int mi = mb; mi < mb + MB; ++mi) {
+                T *c_r = c_mi;
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
+                for (int r = 0; r < 4; ++r) {
+                    const int row = row_base + mi * 16 + r * ROW_STEP;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int row = row_base + mi * 16 + EL::d_row(r, lg), col = col_base + ni * 16;
-                        if (read_c && (!GENERIC || tile_full || (row < M && col < N)))
-                            cin[mi - mb][ni][r] = C[(int64_t)row * ldc + col];
+                    for (int ni = 0; ni < NI; ++ni) {
+                        const int col = col_base + ni * 16;
+                        if (read_c && (!GENERIC || tile_full || (row < M && col < N))) cin[mi - mb][ni][r] = c_r[ni * 16];
                         else cin[mi - mb][ni][r] = T(0);
                     }
+                    c_r += r_step;
+                }
+                c_mi += mi_step;
+            }
+            c_mi = c_mb;
 #pragma unroll
-            for (int mi = mb; mi < mb + MB; ++mi)
+            for (int mi = mb; mi < mb + MB; ++mi) {
+                T *c_r = c_mi;
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
+                for (int r = 0; r < 4; ++r) {
+                    const int row = row_base + mi * 16 + r * ROW_STEP;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int row = row_base + mi * 16 + EL::d_row(r, lg), col = col_base + ni * 16;
+                    for (int ni = 0; ni < NI; ++ni) {
+                        const int col = col_base + ni * 16;
                         if (!GENERIC || tile_full || (row < M && col < N))
-                            C[(int64_t)row * ldc + col] =
-                                UNIT ? cin[mi - mb][ni][r] + acc[mi][ni][r]
-                                     : scaled_update(alpha, acc[mi][ni][r], beta, cin[mi - mb][ni][r], read_c);
+                            c_r[ni * 16] = UNIT ? cin[mi - mb][ni][r] + acc[mi][ni][r]
+                                                : scaled_update(alpha, acc[mi][ni][r], beta, cin[mi - mb][ni][r], read_c);
                     }
+                    c_r += r_step;
+                }
+                c_mi += mi_step;
+            }
+            c_mb += MB * mi_step;
         }
     };
-    if (alpha == T(1) && beta == T(1)) epilogue(std::true_type{});
-    else epilogue(std::false_type{});
+    if (alpha == T(1) && beta == T(1)) epilogue(std::integral_constant<int, kUnit>{});
+    else if (beta == T(0)) epilogue(std::integral_constant<int, kOverwrite>{});
+    else epilogue(std::integral_constant<int, kScaled>{});
 }
 
 // Reference-shaped kernel without tiling or staging: one thread per element of C, k ascending.
