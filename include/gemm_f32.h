@@ -67,6 +67,7 @@ int gemm_f32_general_ex(int transa, int transb, int64_t M, int64_t N, int64_t K,
 int gemm_f32_variant_count(void);
 const char *gemm_f32_variant_name(int variant);
 int gemm_f32_choose_variant(int64_t M, int64_t N, int64_t K, int num_cu);
+int gemm_f32_choose_variant_general(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu);
 
 #ifdef __cplusplus
 }

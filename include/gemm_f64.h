@@ -136,18 +136,30 @@ int gemm_f64_general_ex(int transa, int transb, int64_t M, int64_t N, int64_t K,
                         double beta, double *C, int64_t ldc,
                         void *stream, int variant);
 
-/* Number of kernel variants and their names ("mfma_128x128x16", ...; NULL if out of range). */
+/*
+ * Number of kernel variants and their names ("naive", "mfma_128x128x16", "mfma_64x64x16",
+ * "mfma_128x64x16", "mfma_64x128x16", "mfma_32x64x16", "mfma_64x32x16"; NULL if out of range).
+ * A 32-wide side needs the operand on that side to be contiguous along k: "mfma_32x64x16" exists for
+ * transa == 0 only and "mfma_64x32x16" for transb == 1 only; asking for one with the other layout
+ * returns GEMM_F64_ERR_VARIANT.
+ */
 int gemm_f64_variant_count(void);
 const char *gemm_f64_variant_name(int variant);
 
 /*
  * gemm_f64_choose_variant: the pure host-side selection rule used when
  * variant == -1 (the paper's Section 2.15 Q5 asks how parameters are to be
- * determined; this is a small analytical model over tile quantisation).
+ * determined; this is a small analytical model: per variant, the larger of the tile-quantised makespan
+ * at a measured efficiency and the time one tile needs on its own, which is what counts for problems
+ * of fewer tiles than compute units).
  * num_cu is the number of compute units of the target device (256 on MI355X).
  * Touches no device.
  */
 int gemm_f64_choose_variant(int64_t M, int64_t N, int64_t K, int num_cu);
+
+/* The same rule for transposed operands (it only considers the variants that exist for the layout);
+ * GEMM_F64_ERR_DIM if a flag is not 0 or 1. */
+int gemm_f64_choose_variant_general(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu);
 
 /*
  * gemm_f64_tile_of_block: the workgroup-id -> C-tile mapping used by the MFMA

@@ -57,6 +57,9 @@ def load():
     lib.gemm_f32_variant_name.restype = ctypes.c_char_p
     lib.gemm_f32_choose_variant.argtypes = [i64, i64, i64, ci]
     lib.gemm_f32_choose_variant.restype = ci
+    for fn in (lib.gemm_f64_choose_variant_general, lib.gemm_f32_choose_variant_general):
+        fn.argtypes = [ci, ci, i64, i64, i64, ci]
+        fn.restype = ci
     cd, cf = ctypes.c_double, ctypes.c_float
     lib.gemm_f64_general.argtypes = [ci, ci, i64, i64, i64, cd, vp, i64, vp, i64, cd, vp, i64, vp]
     lib.gemm_f64_general.restype = ci
@@ -122,6 +125,14 @@ def gemm_f64_variant_name(variant: int):
 
 def gemm_f64_choose_variant(M, N, K, num_cu=256) -> int:
     return int(load().gemm_f64_choose_variant(M, N, K, int(num_cu)))
+
+
+def gemm_f64_choose_variant_general(transa, transb, M, N, K, num_cu=256) -> int:
+    return int(load().gemm_f64_choose_variant_general(int(transa), int(transb), M, N, K, int(num_cu)))
+
+
+def gemm_f32_choose_variant_general(transa, transb, M, N, K, num_cu=256) -> int:
+    return int(load().gemm_f32_choose_variant_general(int(transa), int(transb), M, N, K, int(num_cu)))
 
 
 def gemm_f64_tile_of_block(block, tiles_m, tiles_n):

@@ -17,20 +17,36 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 
-def build(verbose: bool = False, save_temps_dir: str = None) -> str:
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [HIPCC, *FLAGS, *SOURCES, "-o", tmp]
-    if save_temps_dir:
-        os.makedirs(save_temps_dir, exist_ok=True)
-        cmd += ["-save-temps=obj"]
-    res = subprocess.run(cmd, capture_output=True, text=True, cwd=save_temps_dir or None)
+def build(verbose: bool = False) -> str:
+    """Compile every source to an object (in parallel: one hipcc per file) and link them into the library."""
+    from concurrent.futures import ThreadPoolExecutor
     noise = "is not a recognized feature for this target"
-    err = "\n".join(ln for ln in res.stderr.splitlines() if noise not in ln)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err.strip():
-        print(err)
-    os.replace(tmp, LIB)
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+
+    def compile_one(src):
+        obj = os.path.join(HERE, os.path.basename(src) + ".%d.o" % os.getpid())
+        res = subprocess.run([HIPCC, *compile_flags, "-c", src, "-o", obj], capture_output=True, text=True)
+        err = "\n".join(ln for ln in res.stderr.splitlines() if noise not in ln)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed on %s:\n%s" % (src, err))
+        return obj, err
+
+    objs = []
+    try:
+        with ThreadPoolExecutor(max_workers=len(SOURCES)) as pool:
+            for obj, err in pool.map(compile_one, SOURCES):
+                objs.append(obj)
+                if verbose and err.strip():
+                    print(err)
+        tmp = LIB + ".tmp.%d" % os.getpid()
+        res = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp], capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("link failed:\n" + res.stderr)
+        os.replace(tmp, LIB)
+    finally:
+        for obj in objs:
+            if os.path.exists(obj):
+                os.remove(obj)
     return LIB
 
 

@@ -11,9 +11,11 @@ namespace {
 const Variant kVariants[] = {
     {"naive", 0, 0, 0.0},
     {"mfma_128x128x32", 128, 128, 0.955},
-    {"mfma_64x64x32", 64, 64, 0.915},
-    {"mfma_128x64x32", 128, 64, 0.935},
-    {"mfma_64x128x32", 64, 128, 0.965},
+    {"mfma_64x64x32", 64, 64, 0.925},
+    {"mfma_128x64x32", 128, 64, 0.94},
+    {"mfma_64x128x32", 64, 128, 0.945},
+    {"mfma_32x64x32", 32, 64, 0.85},
+    {"mfma_64x32x32", 64, 32, 0.85},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 }  // namespace
@@ -27,8 +29,13 @@ extern "C" const char *gemm_f32_variant_name(int variant)
 
 extern "C" int gemm_f32_choose_variant(int64_t M, int64_t N, int64_t K, int num_cu)
 {
-    (void)K;
-    return choose_variant(kVariants, kNumVariants, M, N, num_cu);
+    return choose_variant(kVariants, kNumVariants, 0, 0, M, N, K, num_cu);
+}
+
+extern "C" int gemm_f32_choose_variant_general(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu)
+{
+    if ((transa != 0 && transa != 1) || (transb != 0 && transb != 1)) return GEMM_F64_ERR_DIM;
+    return choose_variant(kVariants, kNumVariants, transa, transb, M, N, K, num_cu);
 }
 
 extern "C" int gemm_f32_ex(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,

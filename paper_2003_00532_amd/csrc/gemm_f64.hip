@@ -5,14 +5,18 @@ using namespace gemm_detail;
 
 namespace {
 // Index order is part of the ABI of gemm_f64_ex (tests and the benchmark name variants by index).
-// Efficiencies are measured fractions of the FP64 MFMA peak at 8192^3 on MI355X (the smaller tiles
-// move more bytes per flop through LDS and L2; 64x128 and 128x64 fit three workgroups per CU).
+// Efficiencies are measured fractions of the FP64 MFMA peak on MI355X: at 8192^3 for the four larger
+// tiles (the smaller ones move more bytes per flop through LDS and L2; 64x128 reaches 0.965 on some
+// machines of the pool and 0.915 on others, 128x128 the same on all, hence the order), at 2048^3 for
+// the two 32-wide tiles, which are only ever chosen for problems of that size or below.
 const Variant kVariants[] = {
     {"naive", 0, 0, 0.0},
     {"mfma_128x128x16", 128, 128, 0.955},
-    {"mfma_64x64x16", 64, 64, 0.915},
-    {"mfma_128x64x16", 128, 64, 0.935},
-    {"mfma_64x128x16", 64, 128, 0.965},
+    {"mfma_64x64x16", 64, 64, 0.925},
+    {"mfma_128x64x16", 128, 64, 0.94},
+    {"mfma_64x128x16", 64, 128, 0.945},
+    {"mfma_32x64x16", 32, 64, 0.85},
+    {"mfma_64x32x16", 64, 32, 0.85},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 }  // namespace
@@ -26,8 +30,7 @@ extern "C" const char *gemm_f64_variant_name(int variant)
 
 extern "C" int gemm_f64_choose_variant(int64_t M, int64_t N, int64_t K, int num_cu)
 {
-    (void)K;
-    return choose_variant(kVariants, kNumVariants, M, N, num_cu);
+    return choose_variant(kVariants, kNumVariants, 0, 0, M, N, K, num_cu);
 }
 
 extern "C" int gemm_f64_tile_of_block(int64_t block, int64_t tiles_m, int64_t tiles_n, int64_t *tile_m,
@@ -61,6 +64,12 @@ extern "C" const char *gemm_f64_strerror(int code)
 }
 
 extern "C" int gemm_f64_version(void) { return 300; }
+
+extern "C" int gemm_f64_choose_variant_general(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu)
+{
+    if ((transa != 0 && transa != 1) || (transb != 0 && transb != 1)) return GEMM_F64_ERR_DIM;
+    return choose_variant(kVariants, kNumVariants, transa, transb, M, N, K, num_cu);
+}
 
 extern "C" int gemm_f64_ex(int64_t M, int64_t N, int64_t K, const double *A, int64_t lda, const double *B,
                            int64_t ldb, double *C, int64_t ldc, void *stream, int variant)

@@ -22,22 +22,46 @@ struct Variant {
 // barrier or in its prologue/epilogue (measured: 2048^3 fp64 as 256 tiles of 128x128 reaches 80 %).
 constexpr double kSingleWorkgroupPenalty = 0.84;
 
+// What a tile costs besides its MFMAs when it runs on its own (fetching the first stages, reading and
+// writing C), in MFMA issue slots; it only matters for problems of a few tiles.
+constexpr double kTileOverheadSlots = 96.0;
+
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Tile quantisation model: workgroups are spread over the compute units, so the makespan is about
-// ceil(tiles / CUs) macro-tiles of work per CU; a smaller tile wastes less at the edges and balances
-// better but runs its inner loop a little less efficiently.  Variant 0 (untiled) is never chosen.
-inline int choose_variant(const Variant *variants, int count, int64_t M, int64_t N, int num_cu)
+// A 32-wide panel exists only for an operand whose k index is contiguous in memory (A as given, B
+// stored transposed), so the 32-row variants need transa == 0 and the 32-column ones transb == 1.
+inline bool variant_available(const Variant &v, int transa, int transb)
+{
+    if (v.bm == 32 && transa) return false;
+    if (v.bn == 32 && !transb) return false;
+    return true;
+}
+
+// Selection model.  Workgroups are spread over the compute units, so the throughput-bound makespan is
+// about ceil(tiles / CUs) macro-tiles of work per CU at the variant's measured efficiency: a smaller
+// tile wastes less at the edges and balances better but runs its inner loop a little less efficiently.
+// It cannot be shorter than the time one tile needs on its own, which is set by the MFMA chain of one
+// wave (K / 4 steps of (BM/32) * (BN/32) instructions, one instruction per unit of time): that floor is
+// what counts when there are fewer tiles than compute units.  Both are in units of one MFMA issue slot
+// of a SIMD.  Variant 0 (untiled) is never chosen.
+inline int choose_variant(const Variant *variants, int count, int transa, int transb, int64_t M, int64_t N, int64_t K,
+                          int num_cu)
 {
     if (num_cu < 1) num_cu = 1;
     if (M <= 0 || N <= 0) return 1;
+    if (K < 1) K = 1;
     int best = 1;
     double best_cost = 0.0;
     for (int v = 1; v < count; ++v) {
         const Variant &var = variants[v];
+        if (!variant_available(var, transa, transb)) continue;
         const int64_t tiles = ceil_div(M, var.bm) * ceil_div(N, var.bn);
         const double eff = var.efficiency * (tiles <= num_cu ? kSingleWorkgroupPenalty : 1.0);
-        const double cost = (double)ceil_div(tiles, num_cu) * var.bm * var.bn / eff;
+        // per SIMD: a macro-tile is (bm * bn / 256) accumulator tiles per wave ... x 4 waves on 4 SIMDs
+        const double wave_chain = (double)(var.bm / 32) * (var.bn / 32);   // MFMAs per k-step in one wave
+        const double throughput = (double)ceil_div(tiles, num_cu) * wave_chain / eff;
+        const double floor_alone = wave_chain + kTileOverheadSlots / (double)ceil_div(K, 4);
+        const double cost = throughput > floor_alone ? throughput : floor_alone;
         if (v == 1 || cost < best_cost) {
             best = v;
             best_cost = cost;
@@ -166,13 +190,22 @@ int gemm_ex(const Variant *variants, int count, int transa, int transb, int64_t 
         err = launch_scale<T>(m, n, beta, C, ldc, stream);
         return err == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
     }
-    if (variant == -1) variant = choose_variant(variants, count, M, N, current_cu_count());
+    if (variant == -1) variant = choose_variant(variants, count, transa, transb, M, N, K, current_cu_count());
+    else if (variant > 0 && !variant_available(variants[variant], transa, transb)) return GEMM_F64_ERR_VARIANT;
     switch (variant) {
     case 0: err = launch_naive<T>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
     case 1: err = launch_mfma<T, 128, 128, 2, 2>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
     case 2: err = launch_mfma<T, 64, 64, 2, 2>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
     case 3: err = launch_mfma<T, 128, 64, 2, 2>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
     case 4: err = launch_mfma<T, 64, 128, 2, 2>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
+    case 5:  // 32-row tiles: A must be k-contiguous
+        err = transb ? launch_mfma_t<T, 32, 64, 2, 2, false, true>(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream)
+                     : launch_mfma_t<T, 32, 64, 2, 2, false, false>(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+        break;
+    case 6:  // 32-column tiles: B must be k-contiguous
+        err = transa ? launch_mfma_t<T, 64, 32, 2, 2, true, true>(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream)
+                     : launch_mfma_t<T, 64, 32, 2, 2, false, true>(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+        break;
     default: return GEMM_F64_ERR_VARIANT;
     }
     return err == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;

@@ -174,7 +174,9 @@ struct Panel {
     static constexpr int E = EL::E;
     static constexpr int SZ = (int)sizeof(T);
     static constexpr int BK = 8 * E;
-    static_assert(BX == 64 || BX == 128, "supported panel widths");
+    // 32-wide panels exist for the k-contiguous kind only (a 1 KiB load of the other kind would span two
+    // groups of rows)
+    static_assert(BX == 64 || BX == 128 || (BX == 32 && KMAJOR), "supported panel widths");
     // KMAJOR
     static constexpr int CHUNKS = (BX / 16) * 2;
     static constexpr int CHUNKS_PER_WAVE = CHUNKS / 4;
@@ -186,14 +188,18 @@ struct Panel {
     static constexpr int LOADS_PER_WAVE = LOADS / 4;
     static constexpr int RPI = 1024 / ROW;             // k rows covered by one such load
     static constexpr int LPR = 64 / RPI;               // lanes per row in it
-    static_assert(RPI >= 1 && RPI <= E && E % RPI == 0, "a load stays inside one group of rows");
+    static_assert(KMAJOR || (RPI >= 1 && RPI <= E && E % RPI == 0), "a load stays inside one group of rows");
     static constexpr int Q_GROUPS = (4 * RPI) / E;
-    static_assert((4 * RPI) % E == 0, "loads of one wave are whole groups apart");
+    static_assert(KMAJOR || (4 * RPI) % E == 0, "loads of one wave are whole groups apart");
     static constexpr int CPR = BX / E;                 // cells per k row
     static_assert(64 % CPR == 0, "a wave covers whole rows of cells");
 
     static constexpr int STAGE_BYTES = KMAJOR ? CHUNKS * 1024 : 8 * GROUP;
     static constexpr int NR = BX / 32;                 // 16-byte cells per thread per stage on the VGPR path
+    // VGPR path, k-contiguous kind: which cell (row in the panel, cell index along k) thread (w, lg, li)
+    // handles as its q-th; 256 threads cover 32 rows x 8 cells at a time
+    __device__ __forceinline__ int vg_row(int q) const { return BX == 32 ? li + 16 * (w & 1) : li + 16 * w + 64 * (q >> 1); }
+    __device__ __forceinline__ int vg_cell(int q) const { return BX == 32 ? lg + 4 * (w >> 1) : lg + 4 * (q & 1); }
 
     const T *P;
     int64_t ld;
@@ -270,7 +276,7 @@ struct Panel {
 #pragma unroll
         for (int q = 0; q < NR; ++q) {
             if constexpr (KMAJOR) {
-                const int row = x0 + li + 16 * w + 64 * (q >> 1), k = k0 + E * (lg + 4 * (q & 1));
+                const int row = x0 + vg_row(q), k = k0 + E * vg_cell(q);
                 const T *p = P + (int64_t)row * ld + k;
 #pragma unroll
                 for (int e = 0; e < E; ++e) r[E * q + e] = (row < X && k + e < K) ? p[e] : T(0);
@@ -291,7 +297,7 @@ struct Panel {
 #pragma unroll
             for (int e = 0; e < E; ++e) v[e] = r[E * q + e];
             if constexpr (KMAJOR) {
-                const int i = li + 16 * w + 64 * (q >> 1), kc = lg + 4 * (q & 1);
+                const int i = vg_row(q), kc = vg_cell(q);
                 *reinterpret_cast<cell_t *>(stage + (((i >> 4) << 1) | (kc >> 2)) * 1024 + (kc & 3) * 256 + (i & 15) * 16) = v;
             } else {
                 const int kk = l / CPR + (64 / CPR) * w + (kThreads / CPR) * q, xc = l % CPR;
@@ -338,6 +344,8 @@ struct Panel {
 // and handles edge tiles.
 // MODE = kStaged is for unaligned operands: every stage goes through VGPRs, loaded two stages ahead
 // and written to LDS one stage ahead, at the price of 16 to 32 more live registers.
+// (Asking the compiler for more than two waves per SIMD was measured to cost 3 to 25 % on the larger
+// tiles: it then schedules the K loop differently; the smaller tiles fit more waves anyway.)
 template <typename T, int BM, int BN, int WM, int WN, int MODE, bool TA, bool TB>
 __global__ void __launch_bounds__(kThreads, 2)
 gemm_mfma_kernel(int M, int N, int K, T alpha, const T *__restrict__ A, int64_t lda, const T *__restrict__ B,

@@ -109,6 +109,47 @@ def test_general_small_shapes_elementwise(gpu_device, variant, combo, dtype):
                     check_general(ta, tb, alpha, As, Bs, beta, C0, c2[:, :N], kind == "int", what)
 
 
+THIN = [(5, (0, 0)), (5, (0, 1)), (6, (0, 1)), (6, (1, 1))]   # 32-row tiles need A as given, 32-column tiles a transposed B
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+@pytest.mark.parametrize("variant,combo", THIN, ids=lambda x: str(x))
+def test_thin_tile_variants_elementwise(gpu_device, variant, combo, dtype):
+    ta, tb = combo
+    with pins.precision(dtype):
+        for n, (M, N, K) in enumerate(SHAPES + [(31, 33, 40), (95, 97, 200)]):
+            for kind in ("int", "uniform"):
+                alpha, beta = SCALARS[(n + variant) % len(SCALARS)]
+                if kind == "int":
+                    alpha, beta = float(round(2 * alpha)), float(round(2 * beta))
+                for pad in ((0, 0, 0), (8, 4, 2), (3, 5, 1)):
+                    A, B, C0 = pg._logical(400 + n, M, N, K, kind="int" if kind == "int" else "uniform")
+                    Ab, As = pg.stored(A, ta, pad=pad[0])
+                    Bb, Bs = pg.stored(B, tb, pad=pad[1])
+                    Cb, _ = pg.stored(C0, 0, pad=pad[2])
+                    a2, b2, c2 = run_general(ta, tb, alpha, Ab, Bb, beta, Cb, M, N, K, variant=variant)
+                    what = "thin variant %d %s %s trans %s pad %s" % (variant, kind, (M, N, K), combo, pad)
+                    assert synth.padding_intact(c2, N) and synth.padding_intact(a2, As.shape[1]) and \
+                        synth.padding_intact(b2, Bs.shape[1]), what
+                    check_general(ta, tb, alpha, As, Bs, beta, C0, c2[:, :N], kind == "int", what)
+
+
+def test_thin_tile_variants_are_refused_for_the_other_layouts(gpu_device):
+    d = torch.zeros(64 * 64, dtype=torch.float64, device="cuda:0")
+    for variant, bad in ((5, [(1, 0), (1, 1)]), (6, [(0, 0), (1, 0)])):
+        for (ta, tb) in bad:
+            assert binding.gemm_f64_general_raw(ta, tb, 64, 64, 64, 1.0, d, 64, d, 64, 1.0, d, 64, variant=variant) == -9
+
+
+@pytest.mark.parametrize("variant", [5])
+def test_thin_tiles_on_the_edge_config(gpu_device, variant):
+    w = synth.WORKLOADS["c2_edge"]
+    Ab, Bb, Cb = synth.workload_inputs(w, seed=1, integer=True)
+    a2, b2, c2 = gpu_util.run_device(Ab, Bb, Cb, w.M, w.N, w.K, variant=variant)
+    assert synth.padding_intact(c2, w.N)
+    gpu_util.check_against_oracle(Ab[:, :w.K], Bb[:, :w.N], Cb[:, :w.N], c2[:, :w.N], True, "c2 variant %d" % variant)
+
+
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 @pytest.mark.parametrize("combo", COMBOS[1:], ids=["nt", "tn", "tt"])
 @pytest.mark.parametrize("variant", MFMA_VARIANTS)

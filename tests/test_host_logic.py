@@ -25,7 +25,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(binding.LIB_PATH)
     names = declared_functions()
-    assert "gemm_f64" in names and "gemm_f64_ex" in names and "gemm_f32" in names and len(names) >= 17
+    assert "gemm_f64" in names and "gemm_f64_ex" in names and "gemm_f32" in names and len(names) >= 19
     for n in names:
         assert hasattr(lib, n), "libgemm_f64.so does not export " + n
     for n in names:
@@ -96,14 +96,36 @@ def test_tile_mapping_keeps_an_xcd_compact():
 
 def test_variant_selection_follows_tile_quantisation():
     name = lambda M, N, K: binding.gemm_f64_variant_name(binding.gemm_f64_choose_variant(M, N, K, 256))
-    assert name(8192, 8192, 8192) == "mfma_64x128x16"
-    # 2088 x 2049 needs 289 tiles of 128x128, two rounds on 256 compute units at ~56 % use: a smaller tile wins
-    assert name(2088, 2049, 2047) == "mfma_64x64x16"
+    # large problems: the tile with the least traffic per flop
+    assert name(8192, 8192, 8192) == "mfma_128x128x16"
+    # 2088 x 2049 needs 289 tiles of 128x128, two rounds on 256 compute units at ~56 % use, and 1089 of 64x64,
+    # five rounds at 85 %: the 32x64 tile (2178 tiles, nine rounds at 94.5 %) wins
+    assert name(2088, 2049, 2047) == "mfma_32x64x16"
     # 2048^2 as 256 tiles of 128x128 leaves every compute unit with a single workgroup
     assert name(2048, 2048, 2048) != "mfma_128x128x16"
+    # a handful of tiles: what counts is the time of one tile on its own, so the smallest tile
+    assert name(256, 256, 256) == "mfma_32x64x16"
     for (M, N, K) in [(1, 1, 1), (256, 256, 256), (2048, 2048, 2048), (16384, 16384, 256), (100000, 3, 7)]:
         v = binding.gemm_f64_choose_variant(M, N, K, 256)
         assert 1 <= v < binding.gemm_f64_variant_count()
+
+
+def test_variant_selection_respects_the_layouts_a_variant_exists_for():
+    vname = binding.gemm_f64_variant_name
+    for (M, N, K) in [(256, 256, 256), (2088, 2049, 2047), (64, 64, 4096), (8192, 8192, 8192), (33, 4000, 100)]:
+        for ta in (0, 1):
+            for tb in (0, 1):
+                for choose, nm in ((binding.gemm_f64_choose_variant_general, binding.gemm_f64_variant_name),
+                                   (binding.gemm_f32_choose_variant_general, binding.gemm_f32_variant_name)):
+                    v = nm(choose(ta, tb, M, N, K, 256))
+                    assert not (v.startswith("mfma_32x") and ta), (v, ta, tb)
+                    assert not ("x32x" in v and not tb), (v, ta, tb)
+    assert vname(binding.gemm_f64_choose_variant_general(0, 0, 256, 256, 256)) == vname(binding.gemm_f64_choose_variant(256, 256, 256))
+    assert binding.gemm_f64_choose_variant_general(2, 0, 256, 256, 256) == -1
+    # explicit requests for a variant that does not exist for the layout are refused before any launch
+    p = 0x1000
+    assert binding.gemm_f64_general_raw(1, 0, 64, 64, 64, 1.0, p, 64, p, 64, 1.0, p, 64, variant=5) == -9
+    assert binding.gemm_f64_general_raw(0, 0, 64, 64, 64, 1.0, p, 64, p, 64, 1.0, p, 64, variant=6) == -9
 
 
 def test_single_precision_entry_points_validate_like_the_double_ones():
@@ -119,7 +141,7 @@ def test_single_precision_entry_points_validate_like_the_double_ones():
     assert raw(0, 5, 5, None, 5, None, 5, None, 5) == 0
     n = binding.gemm_f32_variant_count()
     names = [binding.gemm_f32_variant_name(v) for v in range(n)]
-    assert names[0] == "naive" and all(nm.endswith("x32") for nm in names[1:])
+    assert names[0] == "naive" and all(nm.endswith("x32") for nm in names[1:]) and len(names) == 7
     for (M, N, K) in [(1, 1, 1), (2048, 2048, 2048), (8192, 8192, 8192), (2088, 2049, 2047)]:
         assert 1 <= binding.gemm_f32_choose_variant(M, N, K, 256) < n
 
