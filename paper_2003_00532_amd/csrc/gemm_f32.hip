@@ -9,13 +9,13 @@ namespace {
 // Index order is part of the ABI of gemm_f32_ex.  One LDS stage holds 32 values of k in float.
 // Efficiencies: measured fractions of the FP32 MFMA peak at 8192^3 on MI355X.
 const Variant kVariants[] = {
-    {"naive", 0, 0, 0.0},
-    {"mfma_128x128x32", 128, 128, 0.955},
-    {"mfma_64x64x32", 64, 64, 0.925},
-    {"mfma_128x64x32", 128, 64, 0.94},
-    {"mfma_64x128x32", 64, 128, 0.945},
-    {"mfma_32x64x32", 32, 64, 0.85},
-    {"mfma_64x32x32", 64, 32, 0.85},
+    {"naive", 0, 0, 0.0, 1, 0.0},
+    {"mfma_128x128x32", 128, 128, 0.955, 2, 286.0},
+    {"mfma_64x64x32", 64, 64, 0.925, 4, 55.0},
+    {"mfma_128x64x32", 128, 64, 0.94, 3, 119.0},
+    {"mfma_64x128x32", 64, 128, 0.945, 3, 109.0},
+    {"mfma_32x64x32", 32, 64, 0.85, 6, 25.0},
+    {"mfma_64x32x32", 64, 32, 0.85, 6, 25.0},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 }  // namespace

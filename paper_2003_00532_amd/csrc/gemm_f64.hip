@@ -10,13 +10,13 @@ namespace {
 // machines of the pool and 0.915 on others, 128x128 the same on all, hence the order), at 2048^3 for
 // the two 32-wide tiles, which are only ever chosen for problems of that size or below.
 const Variant kVariants[] = {
-    {"naive", 0, 0, 0.0},
-    {"mfma_128x128x16", 128, 128, 0.955},
-    {"mfma_64x64x16", 64, 64, 0.925},
-    {"mfma_128x64x16", 128, 64, 0.94},
-    {"mfma_64x128x16", 64, 128, 0.945},
-    {"mfma_32x64x16", 32, 64, 0.85},
-    {"mfma_64x32x16", 64, 32, 0.85},
+    {"naive", 0, 0, 0.0, 1, 0.0},
+    {"mfma_128x128x16", 128, 128, 0.955, 2, 286.0},
+    {"mfma_64x64x16", 64, 64, 0.925, 4, 55.0},
+    {"mfma_128x64x16", 128, 64, 0.94, 3, 119.0},
+    {"mfma_64x128x16", 64, 128, 0.945, 3, 109.0},
+    {"mfma_32x64x16", 32, 64, 0.85, 6, 25.0},
+    {"mfma_64x32x16", 64, 32, 0.85, 6, 25.0},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 }  // namespace

@@ -13,18 +13,27 @@ namespace gemm_detail {
 struct Variant {
     const char *name;
     int bm, bn;  // macro-tile; 0 for the untiled kernel
-    // measured fraction of the MFMA peak reached by this tile shape on a large square problem,
-    // used by the selection model
+    // measured fraction of the MFMA peak reached by this tile shape when every compute unit holds as
+    // many of its workgroups as fit, used by the selection model
     double efficiency;
+    int resident;  // workgroups of this shape that fit on one compute unit (registers and LDS decide)
+    // MFMA issue slots per tile that its prologue and epilogue cost beyond the K loop when the compute
+    // units are full (fitted on 16384^2 x 256, checked on 6144^2 x 1024 and 1024 x 8192 x 512)
+    double overhead;
 };
 
-// A compute unit that holds a single workgroup has nothing to run while that workgroup waits at its
-// barrier or in its prologue/epilogue (measured: 2048^3 fp64 as 256 tiles of 128x128 reaches 80 %).
-constexpr double kSingleWorkgroupPenalty = 0.84;
+// With fewer workgroups on a compute unit than fit, there are fewer waves to run while one waits at its
+// barrier or in its prologue/epilogue.  Measured at 2048^3 in double: one resident workgroup of 128x128
+// reaches 0.84 of what two do; two of 64x128 reach 0.92 of what three do.
+inline double few_resident_penalty(int resident_now, int resident_full)
+{
+    if (resident_now >= resident_full) return 1.0;
+    return resident_now <= 1 ? 0.84 : resident_now == 2 ? 0.92 : 0.96;
+}
 
 // What a tile costs besides its MFMAs when it runs on its own (fetching the first stages, reading and
 // writing C), in MFMA issue slots; it only matters for problems of a few tiles.
-constexpr double kTileOverheadSlots = 96.0;
+constexpr double kLoneTileSlots = 96.0;
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
@@ -37,30 +46,33 @@ inline bool variant_available(const Variant &v, int transa, int transb)
     return true;
 }
 
-// Selection model.  Workgroups are spread over the compute units, so the throughput-bound makespan is
-// about ceil(tiles / CUs) macro-tiles of work per CU at the variant's measured efficiency: a smaller
-// tile wastes less at the edges and balances better but runs its inner loop a little less efficiently.
-// It cannot be shorter than the time one tile needs on its own, which is set by the MFMA chain of one
-// wave (K / 4 steps of (BM/32) * (BN/32) instructions, one instruction per unit of time): that floor is
-// what counts when there are fewer tiles than compute units.  Both are in units of one MFMA issue slot
-// of a SIMD.  Variant 0 (untiled) is never chosen.
+// Selection model, in units of one MFMA issue slot of a SIMD (64 cycles in double).  A macro-tile costs
+// each of its four waves (BM/32) * (BN/32) MFMAs per k-step at the variant's measured efficiency, plus
+// what is not hidden of its prologue and epilogue (a measured number of slots per variant: it grows with
+// the outputs per tile and is larger where fewer workgroups share a compute unit).  Workgroups are spread over the compute
+// units, so the throughput-bound makespan is ceil(tiles / CUs) such tiles: a smaller tile wastes less at
+// the edges and balances better but runs its inner loop a little less efficiently.  The makespan cannot
+// be shorter than the time one tile needs on its own (the MFMA chain of one wave plus a fixed start-up
+// and write-back cost): that floor is what counts when there are fewer tiles than compute units.
+// Variant 0 (untiled) is never chosen.
 inline int choose_variant(const Variant *variants, int count, int transa, int transb, int64_t M, int64_t N, int64_t K,
                           int num_cu)
 {
     if (num_cu < 1) num_cu = 1;
     if (M <= 0 || N <= 0) return 1;
     if (K < 1) K = 1;
+    const double ksteps = (double)ceil_div(K, 4);
     int best = 1;
     double best_cost = 0.0;
     for (int v = 1; v < count; ++v) {
         const Variant &var = variants[v];
         if (!variant_available(var, transa, transb)) continue;
         const int64_t tiles = ceil_div(M, var.bm) * ceil_div(N, var.bn);
-        const double eff = var.efficiency * (tiles <= num_cu ? kSingleWorkgroupPenalty : 1.0);
-        // per SIMD: a macro-tile is (bm * bn / 256) accumulator tiles per wave ... x 4 waves on 4 SIMDs
+        const int64_t per_cu = ceil_div(tiles, num_cu);
+        const double eff = var.efficiency * few_resident_penalty(per_cu < var.resident ? (int)per_cu : var.resident, var.resident);
         const double wave_chain = (double)(var.bm / 32) * (var.bn / 32);   // MFMAs per k-step in one wave
-        const double throughput = (double)ceil_div(tiles, num_cu) * wave_chain / eff;
-        const double floor_alone = wave_chain + kTileOverheadSlots / (double)ceil_div(K, 4);
+        const double throughput = (double)per_cu * (wave_chain * ksteps / eff + var.overhead);
+        const double floor_alone = wave_chain * ksteps + kLoneTileSlots;
         const double cost = throughput > floor_alone ? throughput : floor_alone;
         if (v == 1 || cost < best_cost) {
             best = v;
