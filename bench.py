@@ -10,6 +10,7 @@ done for the single-precision path (gemm_f32, FP32 MFMA peak 157.3 TFLOP/s, floa
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_8192] [--variant -1] [--dtype f64|f32]
     python bench.py --copy-calibration     # plain device copy of known size, for scaling rocprof counters
+    python bench.py --compare-vendor       # adds the vendor BLAS (torch.addmm) timed on the same buffers, as context
 """
 import argparse
 import json
@@ -92,6 +93,8 @@ def main():
     ap.add_argument("--dtype", choices=["f64", "f32"], default="f64")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true")
+    ap.add_argument("--compare-vendor", action="store_true",
+                    help="after the measurement, time the vendor BLAS behind torch.addmm on the same buffers (context only)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -185,6 +188,25 @@ def main():
                      "kernel_ms_min": round(min(per_launch_ms), 4), "kernel_ms_max": round(max(per_launch_ms), 4),
                      "algorithmic_flops_per_launch": w.flops, "algorithmic_bytes_per_launch": alg_bytes},
     }
+    if args.compare_vendor:
+        # Context, never the product path: the library routine behind torch.addmm (rocBLAS / hipBLASLt) on the
+        # same operands, timed the same way after the measurement above is complete (dense views only).
+        if w.lda == w.K and w.ldb == w.N and w.ldc == w.N:
+            n = max(3, min(args.steps, 20))
+            for _ in range(3):
+                torch.addmm(dC, dA, dB, out=dC)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(n):
+                torch.addmm(dC, dA, dB, out=dC)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            vms = e0.elapsed_time(e1) / n
+            out["vendor_blas_context"] = {"value": round(w.flops / (vms * 1e-3) / 1e9, 1), "unit": "GFLOP/s",
+                                          "ms_per_call": round(vms, 4), "what": "torch.addmm on the same buffers, comparison only"}
+        else:
+            out["vendor_blas_context"] = None
     if not args.no_cpu_baseline:
         t0 = time.perf_counter()
         out["cpu_baseline"] = cpu_baseline(w, args.seed, np_dtype=np_dtype)
