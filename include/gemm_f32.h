@@ -10,9 +10,8 @@
  * Everything stated in gemm_f64.h about argument meaning, layout, ownership, asynchrony, aliasing,
  * edge handling and error behaviour holds here with `float` for `double`; the return codes are the
  * GEMM_F64_* values of that header.  Differences:
- *   - pointers must be 4-byte aligned; the asynchronous 16-byte global->LDS path needs 16-byte
- *     aligned A and B and lda, ldb that are multiples of 4, otherwise a slower register-staged
- *     variant of the same kernel runs (same result);
+ *   - pointers must be 4-byte aligned, nothing more; leading dimensions of 2^23 or more elements
+ *     switch to the slower 64-bit-addressing variant of the kernel (same result);
  *   - arithmetic is binary32 throughout (FP32 MFMA, four k per instruction, accumulated from zero,
  *     C added once at the end): bit-identical to the sequential binary32 nest whenever every
  *     partial sum is exact (e.g. integer data with |sum| < 2^24), and within

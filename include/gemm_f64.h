@@ -55,9 +55,11 @@ enum {
  * never written, and nothing past the last logical element of the last row is
  * touched.  C must not overlap A or B; A and B may alias each other.
  *
- * Alignment: pointers must be 8-byte aligned.  When A and B are 16-byte aligned
- * and lda, ldb are even the panels are fetched with 128-bit loads; otherwise a
- * 64-bit-load variant of the same kernel is used (same result, slower).
+ * Alignment: pointers must be 8-byte aligned; nothing more is asked.  Operands
+ * with odd leading dimensions or bases that are not 16-byte aligned run the
+ * same kernel (its 16-byte global->LDS copies only need element alignment).
+ * Leading dimensions of 2^22 or more elements switch to a slower variant of
+ * the kernel that addresses memory with 64-bit pointers (same result).
  *
  * Arithmetic: binary64 throughout.  Products are accumulated from zero in the
  * matrix unit, four k at a time, and C is added once at the end, so the
@@ -120,8 +122,7 @@ int gemm_f64_ex(int64_t M, int64_t N, int64_t K,
  * 1e-13 * (|alpha| * sum_k |opA(i,k) * opB(k,j)| + |beta * C_in|) otherwise.
  *
  * Transposed operands change only how panels are brought into LDS; all four
- * combinations run the same MFMA kernel at the same speed class.  The 128-bit
- * asynchronous path needs 16-byte aligned A and B and even lda, ldb.
+ * combinations run the same MFMA kernel at the same speed class.
  */
 int gemm_f64_general(int transa, int transb, int64_t M, int64_t N, int64_t K,
                      double alpha, const double *A, int64_t lda,

@@ -106,15 +106,15 @@ int validate(int transa, int transb, int64_t M, int64_t N, int64_t K, bool ab_re
     return GEMM_F64_OK;
 }
 
-// 16-byte global->LDS copies need 16-byte aligned bases and leading dimensions that are multiples of
-// the elements per 16 bytes; their per-lane byte offsets (up to 128 stored rows) are 32-bit, which
-// bounds the leading dimensions.
+// The 16-byte global->LDS copies take any address that is aligned to the element (measured: an 8-byte
+// aligned double operand with an odd leading dimension is copied correctly and at nearly full speed), so
+// alignment never decides the path.  What does is the 32-bit per-lane byte offset of those copies, which
+// spans up to 128 stored rows: the leading dimensions must stay below 2^32 / (128 * sizeof(T)).
 template <typename T>
-bool async_copies_possible(const T *A, int64_t lda, const T *B, int64_t ldb)
+bool async_copies_possible(int64_t lda, int64_t ldb)
 {
-    constexpr int64_t E = 16 / sizeof(T);
-    return (((uintptr_t)A | (uintptr_t)B) & 15u) == 0 && (lda % E == 0) && (ldb % E == 0) && lda < (1 << 20) &&
-           ldb < (1 << 20);
+    constexpr int64_t limit = ((int64_t)1 << 32) / (128 * (int64_t)sizeof(T));
+    return lda < limit && ldb < limit;
 }
 
 template <typename T, int BM, int BN, int WM, int WN, bool TA, bool TB>
@@ -124,8 +124,8 @@ hipError_t launch_mfma_t(int M, int N, int K, T alpha, const T *A, int64_t lda, 
     constexpr int BK = 8 * (16 / (int)sizeof(T));
     const int tiles_m = (int)ceil_div(M, BM), tiles_n = (int)ceil_div(N, BN);
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(kThreads);
-    const bool vec = async_copies_possible(A, lda, B, ldb);
-    // The lean kernel assumes full tiles everywhere, whole K stages and aligned operands.
+    const bool vec = async_copies_possible<T>(lda, ldb);
+    // The lean kernel assumes full tiles everywhere and whole K stages.
     const bool lean = vec && (M % BM == 0) && (N % BN == 0) && (K % BK == 0);
     if (lean)
         hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kLean, TA, TB>), grid, block, 0, stream, M, N, K, alpha, A,

@@ -156,7 +156,8 @@ __device__ __forceinline__ T scaled_update(T alpha, T s, T beta, T c, bool read_
 // that path is a wave-uniform 64-bit base, advanced with scalar arithmetic, plus a 32-bit per-lane
 // byte offset computed once: MFMAs and ordinary vector ALU instructions compete for the same issue
 // cycles on this chip, so the K loop should contain none of the latter.  (The host only selects the
-// path when 128 * ld, in bytes, fits in 31 bits.)
+// path when 128 * ld, in bytes, fits in 32 bits.)  The copies need the global address aligned to the
+// element only, not to their own 16 bytes.
 //
 // Edges along x (GENERIC only).  KMAJOR: rows at or beyond the extent X are redirected to row X - 1;
 // they only feed outputs that are never stored, so no zero fill is needed and such tiles stay on the
@@ -164,7 +165,7 @@ __device__ __forceinline__ T scaled_update(T alpha, T s, T beta, T c, bool read_
 // LDS cells keep stale bits, which again only feed outputs never stored) and a partly valid last cell
 // is fetched on its own, four bytes per lane.
 //
-// The VGPR path (load_regs / store_regs: ragged last K stage, unaligned operands) loads element-wise,
+// The VGPR path (load_regs / store_regs: ragged last K stage, very large leading dimensions) loads element-wise,
 // with zeros outside the logical matrix, and writes the same LDS layout.  Both operands are zeroed for
 // k >= K, so padding only ever forms 0 * 0.
 template <typename T, bool KMAJOR, int BX, bool GENERIC>
@@ -336,14 +337,15 @@ struct Panel {
 // values of k (16 for double, 32 for float) of the op(A) panel followed by the op(B) panel; see Panel
 // for the layouts.  TA / TB say that A / B is stored transposed (K x M / N x K).
 //
-// MODE = kLean: every tile is full, K is a multiple of BK, A and B are 16-byte aligned with
-// leading dimensions that are multiples of E (checked on the host); only the asynchronous path is
-// compiled in.
+// MODE = kLean: every tile is full and K is a multiple of BK (checked on the host); only the
+// asynchronous path is compiled in.
 // MODE = kGeneric adds the element-wise, zero-filled path through VGPRs for the ragged last K stage
 // (synchronous: once per tile; zeros are required there because k >= K contributes to every output)
 // and handles edge tiles.
-// MODE = kStaged is for unaligned operands: every stage goes through VGPRs, loaded two stages ahead
-// and written to LDS one stage ahead, at the price of 16 to 32 more live registers.
+// MODE = kStaged sends every stage through VGPRs, loaded two stages ahead and written to LDS one stage
+// ahead, at the price of 16 to 32 more live registers and of vector-ALU work in the K loop.  It
+// addresses memory with 64-bit pointers and is what remains for leading dimensions too large for the
+// 32-bit lane offsets of the asynchronous copies.
 // (Asking the compiler for more than two waves per SIMD was measured to cost 3 to 25 % on the larger
 // tiles: it then schedules the K loop differently; the smaller tiles fit more waves anyway.)
 template <typename T, int BM, int BN, int WM, int WN, int MODE, bool TA, bool TB>

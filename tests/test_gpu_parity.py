@@ -34,7 +34,8 @@ def _case(M, N, K, pad, kind, seed):
 @pytest.mark.parametrize("kind", ["int", "uniform"])
 def test_small_shapes_elementwise(gpu_device, variant, kind):
     for n, (M, N, K) in enumerate(SHAPES):
-        # even paddings keep rows 16-byte aligned (128-bit path), odd ones force the 64-bit path
+        # even paddings keep rows 16-byte aligned, odd ones make every other row start 8 bytes off: the
+        # 16-byte global->LDS copies must cope with both
         for pad in ((0, 0, 0), (8, 6, 2), (3, 5, 1)):
             Ab, A, Bb, B, Cb, C = _case(M, N, K, pad, kind, 100 + n)
             a2, b2, c2 = gpu_util.run_device(Ab, Bb, Cb, M, N, K, variant=variant)
@@ -45,7 +46,7 @@ def test_small_shapes_elementwise(gpu_device, variant, kind):
 
 @pytest.mark.parametrize("variant", [-1, 1, 2])
 def test_misaligned_base_pointers(gpu_device, variant):
-    # bases 8 bytes off a 16-byte boundary: the 128-bit path must not be taken
+    # bases 8 bytes off a 16-byte boundary: the 16-byte copies only need element alignment
     M, N, K = 150, 140, 70
     for kind in ("int", "uniform"):
         Ab, A, Bb, B, Cb, C = _case(M, N, K, (2, 2, 2), kind, 7)
@@ -78,6 +79,37 @@ def test_right_and_bottom_edges_on_the_async_path(gpu_device, variant):
         what = "variant %d edge %s" % (variant, (M, N, K))
         assert synth.padding_intact(c2, N) and synth.padding_intact(a2, K) and synth.padding_intact(b2, N), what
         gpu_util.check_against_oracle(A, B, C, c2[:, :N], True, what)
+
+
+@pytest.mark.parametrize("variant", [-1, 1, 2, 5])
+def test_huge_leading_dimension_uses_64_bit_addressing(gpu_device, variant):
+    # lda >= 2^22 elements is beyond the 32-bit lane offsets of the asynchronous copies: the register-staged
+    # mode of the kernel takes over; checked on several shapes inside one 2.2 GB buffer (ragged edges, K tail)
+    ld_big = (1 << 22) + 3
+    rows = 140
+    bufA = torch.full((rows, ld_big), float("nan"), dtype=torch.float64, device="cuda:0")
+    for n, (M, N, K) in enumerate([(140, 70, 100), (64, 64, 64), (65, 130, 33), (129, 31, 17)]):
+        _, A = synth.matrix(50 + n, synth.TAG_A, M, K, None, "int")
+        Bb, B = synth.matrix(50 + n, synth.TAG_B, K, N, N + 1, "int")
+        Cb, C = synth.matrix(50 + n, synth.TAG_C, M, N, N + 3, "int")
+        bufA[:M, :K] = torch.from_numpy(A).to("cuda:0")
+        dB, dC = gpu_util.to_dev(Bb), gpu_util.to_dev(Cb)
+        binding.gemm_f64_ex(M, N, K, bufA, ld_big, dB, N + 1, dC, N + 3, variant=variant)
+        torch.cuda.synchronize()
+        c2 = dC.cpu().numpy()
+        assert synth.padding_intact(c2, N)
+        gpu_util.check_against_oracle(A, B, C, c2[:, :N], True, "huge lda %s variant %d" % ((M, N, K), variant))
+    # and a huge ldb (B rows far apart), A dense
+    K, N, M = 24, 40, 50
+    bufB = torch.full((K, ld_big), float("nan"), dtype=torch.float64, device="cuda:0")
+    _, A = synth.matrix(60, synth.TAG_A, M, K, None, "uniform")
+    _, B = synth.matrix(60, synth.TAG_B, K, N, None, "uniform")
+    Cb, C = synth.matrix(60, synth.TAG_C, M, N, N, "uniform")
+    bufB[:, :N] = torch.from_numpy(B).to("cuda:0")
+    dA, dC = gpu_util.to_dev(A), gpu_util.to_dev(Cb)
+    binding.gemm_f64_ex(M, N, K, dA, K, bufB, ld_big, dC, N, variant=variant)
+    torch.cuda.synchronize()
+    gpu_util.check_against_oracle(A, B, C, dC.cpu().numpy(), False, "huge ldb variant %d" % variant)
 
 
 def test_stale_lds_bits_do_not_reach_valid_columns(gpu_device):

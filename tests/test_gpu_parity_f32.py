@@ -40,8 +40,8 @@ def _case(M, N, K, pad, kind, seed):
 @pytest.mark.parametrize("kind", ["int", "uniform"])
 def test_small_shapes_elementwise(gpu_device, variant, kind):
     for n, (M, N, K) in enumerate(SHAPES):
-        # paddings that make ld a multiple of 4 keep rows 16-byte aligned (async path) for some shapes,
-        # the others force the register-staged path
+        # paddings that make ld a multiple of 4 keep rows 16-byte aligned for some shapes; for the others rows
+        # start 4, 8 or 12 bytes off, which the 16-byte global->LDS copies must cope with
         for pad in ((0, 0, 0), ((-K) % 4 + 4, (-N) % 4 + 8, 2), (3, 5, 1)):
             Ab, A, Bb, B, Cb, C = _case(M, N, K, pad, kind, 100 + n)
             a2, b2, c2 = gpu_util.run_device(Ab, Bb, Cb, M, N, K, variant=variant)

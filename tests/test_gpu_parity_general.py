@@ -95,8 +95,7 @@ def test_general_small_shapes_elementwise(gpu_device, variant, combo, dtype):
                 alpha, beta = SCALARS[(n + ta + 2 * tb) % len(SCALARS)]
                 if kind == "int":
                     alpha, beta = float(round(2 * alpha)), float(round(2 * beta))
-                # pads (0, 0, 0) and (8, 4, 2) keep every stored row 16-byte aligned (asynchronous path),
-                # (3, 5, 1) forces the register-staged path
+                # pads (0, 0, 0) and (8, 4, 2) keep every stored row 16-byte aligned, (3, 5, 1) does not
                 for pad in ((0, 0, 0), (8, 4, 2), (3, 5, 1)):
                     A, B, C0 = pg._logical(300 + n, M, N, K, kind="int" if kind == "int" else "uniform")
                     Ab, As = pg.stored(A, ta, pad=pad[0])
@@ -153,8 +152,8 @@ def test_thin_tiles_on_the_edge_config(gpu_device, variant):
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 @pytest.mark.parametrize("combo", COMBOS[1:], ids=["nt", "tn", "tt"])
 @pytest.mark.parametrize("variant", MFMA_VARIANTS)
-def test_transposed_edges_stay_correct_on_the_async_path(gpu_device, variant, combo, dtype):
-    # aligned operands, leading dimensions that are multiples of four elements: edge tiles in M and N are
+def test_transposed_edges(gpu_device, variant, combo, dtype):
+    # leading dimensions that are multiples of four elements: edge tiles in M and N are
     # handled by row redirection (k-contiguous operand) or by masked cells plus 4-byte tail copies
     # (the other kind), whichever operand they belong to; every remainder class is visited
     ta, tb = combo
