@@ -1,4 +1,5 @@
-// MFMA GEMM kernels for gfx950 (MI355X): C += A * B, row-major, for double and float elements.
+// MFMA GEMM kernels for gfx950 (MI355X): C += A * B, and the full C <- alpha * op(A) * op(B) + beta * C,
+// row-major, for double and float elements.
 //
 // How the paper's scheme maps onto this kernel (Section 2.4 schedule, Sections
 // 2.6, 2.7, 2.9, 2.10, 2.13, 2.14):
