@@ -225,3 +225,31 @@ def test_general_8192_sampled_rows(gpu_device, combo):
     oracle.gemm_general_ref(0, 0, 0.5, Ar, B, 0.0, want)
     S = oracle.general_scale(0, 0, 0.5, Ar, B, 0.0, want)
     print("8192^3 trans %s worst |diff|/S = %.3g" % (combo, gpu_util.check_tolerance(got, want, S, "8192 %s" % (combo,))))
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
+def test_seeded_random_cases_differential(gpu_device, dtype):
+    # 160 seeded cases per precision: random shape (ragged in every dimension, including zero sizes), random
+    # paddings (aligned and not), random transposes, scalars from a set that includes 0 and 1, and a random
+    # kernel variant among those that exist for the layout; integer data, so the bar is bit-exactness
+    rng = np.random.default_rng(20030532)
+    n_variants = binding.gemm_f64_variant_count()
+    scal = [0.0, 1.0, -1.0, 2.0, -3.0, 0.5]
+    with pins.precision(dtype):
+        for case in range(160):
+            M, N = int(rng.integers(0, 200)), int(rng.integers(0, 200))
+            K = int(rng.choice([0, 1, 3, 15, 16, 17, 31, 32, 33, 64, 100, int(rng.integers(1, 260))]))
+            ta, tb = int(rng.integers(2)), int(rng.integers(2))
+            alpha, beta = float(rng.choice(scal)), float(rng.choice(scal))
+            pads = [int(rng.choice([0, 1, 2, 3, 4, 7, 8])) for _ in range(3)]
+            variant = int(rng.integers(-1, n_variants))
+            if (variant == 5 and ta) or (variant == 6 and not tb):
+                variant = -1
+            A, B, C0 = pg._logical(9000 + case, M, N, K, kind="int")
+            Ab, As = pg.stored(A, ta, pad=pads[0])
+            Bb, Bs = pg.stored(B, tb, pad=pads[1])
+            Cb, _ = pg.stored(C0, 0, pad=pads[2])
+            a2, b2, c2 = run_general(ta, tb, alpha, Ab, Bb, beta, Cb, M, N, K, variant=variant)
+            what = "case %d: %s trans %s alpha %g beta %g pads %s variant %d" % (case, (M, N, K), (ta, tb), alpha, beta, pads, variant)
+            assert synth.padding_intact(c2, N) and synth.padding_intact(a2, As.shape[1]) and synth.padding_intact(b2, Bs.shape[1]), what
+            check_general(ta, tb, alpha, As, Bs, beta, C0, c2[:, :N], True, what)
