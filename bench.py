@@ -188,6 +188,20 @@ def main():
                      "kernel_ms_min": round(min(per_launch_ms), 4), "kernel_ms_max": round(max(per_launch_ms), 4),
                      "algorithmic_flops_per_launch": w.flops, "algorithmic_bytes_per_launch": alg_bytes},
     }
+    # What the matrix pipes sustain with no memory traffic at the clock the chip holds (the library's MFMA-only
+    # probe), reported beside the published peak: the kernel's distance from the hardware, not from the data sheet.
+    probe = binding.gemm_f32_mfma_probe if f32 else binding.gemm_f64_mfma_probe
+    sink = torch.empty(512 * props.multi_processor_count, dtype=torch.float32 if f32 else torch.float64, device=dev)
+    iters = 40000 if f32 else 20000
+    probe(iters, sink, sink.numel(), stream=stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    probe_flops = probe(iters, sink, sink.numel(), stream=stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    mfma_only = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    out["roofline"]["mfma_only_tflops"] = round(mfma_only, 2)
+    out["roofline"]["frac_of_mfma_only"] = round(achieved_tflops / mfma_only, 4)
     if args.compare_vendor:
         # Context, never the product path: the library routine behind torch.addmm (rocBLAS / hipBLASLt) on the
         # same operands, timed the same way after the measurement above is complete (dense views only).

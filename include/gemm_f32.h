@@ -68,6 +68,9 @@ const char *gemm_f32_variant_name(int variant);
 int gemm_f32_choose_variant(int64_t M, int64_t N, int64_t K, int num_cu);
 int gemm_f32_choose_variant_general(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu);
 
+/* The float counterpart of gemm_f64_mfma_probe (v_mfma_f32_16x16x4_f32). */
+int gemm_f32_mfma_probe(int64_t iterations, float *sink, int64_t sink_elems, void *stream, double *flops);
+
 #ifdef __cplusplus
 }
 #endif

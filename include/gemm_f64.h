@@ -175,6 +175,18 @@ int gemm_f64_choose_variant_general(int transa, int transb, int64_t M, int64_t N
 int gemm_f64_tile_of_block(int64_t block, int64_t tiles_m, int64_t tiles_n,
                            int64_t *tile_m, int64_t *tile_n);
 
+/*
+ * gemm_f64_mfma_probe: a diagnostic, not part of the operation.  Enqueues a register-resident loop of
+ * independent v_mfma_f64_16x16x4_f64 instructions with no memory traffic (two workgroups of four waves
+ * per compute unit, sixteen accumulator tiles per wave, `iterations` rounds of sixteen instructions),
+ * so that a benchmark can report what the matrix pipes sustain at the clock the chip actually holds
+ * beside the published peak (the paper quotes its numbers against a machine peak in the same way,
+ * Section 1.3).  `sink` is a device buffer of at least 512 * (compute units) elements that receives
+ * one value per thread; *flops (host, may be NULL) receives the floating-point operations of the
+ * launch.  Returns GEMM_F64_ERR_DIM for iterations outside 1 .. 2^30 or a sink that is too small.
+ */
+int gemm_f64_mfma_probe(int64_t iterations, double *sink, int64_t sink_elems, void *stream, double *flops);
+
 /* Static description of a return code; never NULL, never freed. */
 const char *gemm_f64_strerror(int code);
 

@@ -60,6 +60,9 @@ def load():
     for fn in (lib.gemm_f64_choose_variant_general, lib.gemm_f32_choose_variant_general):
         fn.argtypes = [ci, ci, i64, i64, i64, ci]
         fn.restype = ci
+    for fn in (lib.gemm_f64_mfma_probe, lib.gemm_f32_mfma_probe):
+        fn.argtypes = [i64, vp, i64, vp, ctypes.POINTER(ctypes.c_double)]
+        fn.restype = ci
     cd, cf = ctypes.c_double, ctypes.c_float
     lib.gemm_f64_general.argtypes = [ci, ci, i64, i64, i64, cd, vp, i64, vp, i64, cd, vp, i64, vp]
     lib.gemm_f64_general.restype = ci
@@ -205,6 +208,19 @@ def gemm_f32_general_ex(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C,
 def gemm_f32_general_raw(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=0, variant=-1) -> int:
     return int(load().gemm_f32_general_ex(int(transa), int(transb), M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
                                           _ptr(C), ldc, stream, int(variant)))
+
+
+def gemm_f64_mfma_probe(iterations, sink, sink_elems, stream=None) -> float:
+    """Enqueue the MFMA-only probe (double); returns the floating-point operations of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(load().gemm_f64_mfma_probe(int(iterations), _ptr(sink), int(sink_elems), _stream(stream), ctypes.byref(flops)))
+    return float(flops.value)
+
+
+def gemm_f32_mfma_probe(iterations, sink, sink_elems, stream=None) -> float:
+    flops = ctypes.c_double(0.0)
+    _check(load().gemm_f32_mfma_probe(int(iterations), _ptr(sink), int(sink_elems), _stream(stream), ctypes.byref(flops)))
+    return float(flops.value)
 
 
 def variant_index(name: str) -> int:

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgemm_f64.so")
-SOURCES = [os.path.join(CSRC, "gemm_f64.hip"), os.path.join(CSRC, "gemm_f32.hip")]
+SOURCES = [os.path.join(CSRC, "gemm_f64.hip"), os.path.join(CSRC, "gemm_f32.hip"), os.path.join(CSRC, "mfma_probe.hip")]
 DEPENDS = SOURCES + [os.path.join(CSRC, "gemm_mfma.hpp"), os.path.join(CSRC, "gemm_host.hpp"),
                      os.path.join(os.path.dirname(HERE), "include", "gemm_f64.h"),
                      os.path.join(os.path.dirname(HERE), "include", "gemm_f32.h")]

@@ -138,3 +138,20 @@ def test_concurrent_host_threads_on_their_own_streams(gpu_device):
     assert not errors, errors
     for i, (A, B, C, got) in results.items():
         gpu_util.check_against_oracle(A, B, C, got, True, "thread %d" % i)
+
+
+def test_mfma_probe_runs_and_validates_its_arguments(gpu_device):
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.full((512 * cus,), float("nan"), dtype=torch.float64, device=DEV)
+    flops = binding.gemm_f64_mfma_probe(10, sink, sink.numel())
+    torch.cuda.synchronize()
+    assert flops == 2 * cus * 4 * 10 * 16 * 2048.0
+    # every thread wrote a finite value: 4 result elements x 16 tiles, each 10 iterations x 4 k of a*b
+    assert bool(torch.isfinite(sink).all()) and float(sink.min()) > 0
+    assert load_raw().gemm_f64_mfma_probe(10, sink.data_ptr(), sink.numel() - 1, None, None) == -1
+    assert load_raw().gemm_f64_mfma_probe(0, sink.data_ptr(), sink.numel(), None, None) == -1
+    assert load_raw().gemm_f64_mfma_probe(10, None, sink.numel(), None, None) == -5
+
+
+def load_raw():
+    return binding.load()
