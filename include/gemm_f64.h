@@ -138,6 +138,41 @@ int gemm_f64_general_ex(int transa, int transb, int64_t M, int64_t N, int64_t K,
                         void *stream, int variant);
 
 /*
+ * gemm_f64_general_ws: gemm_f64_general with a workspace on offer (the paper's Section 2.15 Q5 asks how tuning
+ * choices are to be made per problem; splitting the k range is the one choice that needs memory).  For problems of
+ * few output tiles and a long k range the library may cut the range into S slices, compute the S partial products
+ * into S dense M x N slabs of the workspace with one launch, and add them up in ascending order in a second launch
+ * (the result is a pure function of the arguments and of the workspace size on offer, never of scheduling).
+ * Whether and how it splits is decided by gemm_f64_split_k_plan; with workspace == NULL, with too little of it or
+ * when splitting would not pay, the call is gemm_f64_general exactly.
+ *
+ *   workspace        device pointer, 8-byte aligned, workspace_bytes long; owned by the caller, used only between
+ *                    the two launches of this call on `stream`, contents undefined afterwards; calls that share a
+ *                    workspace must be ordered (same stream, or synchronised).  May be NULL with workspace_bytes 0.
+ *   workspace_bytes  what the library may use; gemm_f64_split_k_workspace_bytes says what it would like.
+ *
+ * The library still allocates nothing.  Arithmetic: each slice is accumulated from zero in the matrix unit, the
+ * slabs are added in ascending slice order in binary64, then the scalar tail of gemm_f64_general; same tolerance.
+ */
+int gemm_f64_general_ws(int transa, int transb, int64_t M, int64_t N, int64_t K,
+                        double alpha, const double *A, int64_t lda,
+                        const double *B, int64_t ldb,
+                        double beta, double *C, int64_t ldc,
+                        void *workspace, int64_t workspace_bytes, void *stream);
+
+/*
+ * gemm_f64_split_k_plan: the pure host-side rule behind gemm_f64_general_ws (no device is touched).  Writes the
+ * kernel variant, the number of slices (1 = the k range is not split) and the slice length (a multiple of 16;
+ * K itself when not split) that a call with these arguments and this much workspace uses.  num_cu as for
+ * gemm_f64_choose_variant.  Returns GEMM_F64_ERR_DIM for negative sizes or bad flags.
+ */
+int gemm_f64_split_k_plan(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu,
+                          int64_t workspace_bytes, int *variant, int *splits, int *k_chunk);
+
+/* Bytes of workspace the rule would use if it could have any amount (0: it would not split this problem). */
+int64_t gemm_f64_split_k_workspace_bytes(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu);
+
+/*
  * Number of kernel variants and their names ("naive", "mfma_128x128x16", "mfma_64x64x16",
  * "mfma_128x64x16", "mfma_64x128x16", "mfma_32x64x16", "mfma_64x32x16"; NULL if out of range).
  * A 32-wide side needs the operand on that side to be contiguous along k: "mfma_32x64x16" exists for

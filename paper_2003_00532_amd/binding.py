@@ -63,7 +63,18 @@ def load():
     for fn in (lib.gemm_f64_mfma_probe, lib.gemm_f32_mfma_probe):
         fn.argtypes = [i64, vp, i64, vp, ctypes.POINTER(ctypes.c_double)]
         fn.restype = ci
+    ip = ctypes.POINTER(ci)
+    for fn in (lib.gemm_f64_split_k_plan, lib.gemm_f32_split_k_plan):
+        fn.argtypes = [ci, ci, i64, i64, i64, ci, i64, ip, ip, ip]
+        fn.restype = ci
+    for fn in (lib.gemm_f64_split_k_workspace_bytes, lib.gemm_f32_split_k_workspace_bytes):
+        fn.argtypes = [ci, ci, i64, i64, i64, ci]
+        fn.restype = i64
     cd, cf = ctypes.c_double, ctypes.c_float
+    lib.gemm_f64_general_ws.argtypes = [ci, ci, i64, i64, i64, cd, vp, i64, vp, i64, cd, vp, i64, vp, i64, vp]
+    lib.gemm_f64_general_ws.restype = ci
+    lib.gemm_f32_general_ws.argtypes = [ci, ci, i64, i64, i64, cf, vp, i64, vp, i64, cf, vp, i64, vp, i64, vp]
+    lib.gemm_f32_general_ws.restype = ci
     lib.gemm_f64_general.argtypes = [ci, ci, i64, i64, i64, cd, vp, i64, vp, i64, cd, vp, i64, vp]
     lib.gemm_f64_general.restype = ci
     lib.gemm_f64_general_ex.argtypes = [ci, ci, i64, i64, i64, cd, vp, i64, vp, i64, cd, vp, i64, vp, ci]
@@ -221,6 +232,42 @@ def gemm_f32_mfma_probe(iterations, sink, sink_elems, stream=None) -> float:
     flops = ctypes.c_double(0.0)
     _check(load().gemm_f32_mfma_probe(int(iterations), _ptr(sink), int(sink_elems), _stream(stream), ctypes.byref(flops)))
     return float(flops.value)
+
+
+# ---- split K with a caller-provided workspace --------------------------------------------------
+
+def gemm_f64_general_ws(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace, workspace_bytes, stream=None):
+    """gemm_f64_general with a device workspace on offer (the library may split the k range)."""
+    _check(load().gemm_f64_general_ws(int(transa), int(transb), M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                      _ptr(C), ldc, _ptr(workspace), int(workspace_bytes), _stream(stream)))
+
+
+def gemm_f32_general_ws(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace, workspace_bytes, stream=None):
+    _check(load().gemm_f32_general_ws(int(transa), int(transb), M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                      _ptr(C), ldc, _ptr(workspace), int(workspace_bytes), _stream(stream)))
+
+
+def _plan(fn, transa, transb, M, N, K, num_cu, workspace_bytes):
+    v, s, c = ctypes.c_int(-1), ctypes.c_int(-1), ctypes.c_int(-1)
+    _check(fn(int(transa), int(transb), M, N, K, int(num_cu), int(workspace_bytes), ctypes.byref(v), ctypes.byref(s), ctypes.byref(c)))
+    return int(v.value), int(s.value), int(c.value)
+
+
+def gemm_f64_split_k_plan(transa, transb, M, N, K, num_cu=256, workspace_bytes=2 ** 62):
+    """(variant, splits, k_chunk) that gemm_f64_general_ws uses for these arguments."""
+    return _plan(load().gemm_f64_split_k_plan, transa, transb, M, N, K, num_cu, workspace_bytes)
+
+
+def gemm_f32_split_k_plan(transa, transb, M, N, K, num_cu=256, workspace_bytes=2 ** 62):
+    return _plan(load().gemm_f32_split_k_plan, transa, transb, M, N, K, num_cu, workspace_bytes)
+
+
+def gemm_f64_split_k_workspace_bytes(transa, transb, M, N, K, num_cu=256) -> int:
+    return int(load().gemm_f64_split_k_workspace_bytes(int(transa), int(transb), M, N, K, int(num_cu)))
+
+
+def gemm_f32_split_k_workspace_bytes(transa, transb, M, N, K, num_cu=256) -> int:
+    return int(load().gemm_f32_split_k_workspace_bytes(int(transa), int(transb), M, N, K, int(num_cu)))
 
 
 def variant_index(name: str) -> int:

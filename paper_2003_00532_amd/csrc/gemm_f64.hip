@@ -96,3 +96,31 @@ extern "C" int gemm_f64_general(int transa, int transb, int64_t M, int64_t N, in
 {
     return gemm_f64_general_ex(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, -1);
 }
+
+extern "C" int gemm_f64_general_ws(int transa, int transb, int64_t M, int64_t N, int64_t K, double alpha, const double *A,
+                                   int64_t lda, const double *B, int64_t ldb, double beta, double *C, int64_t ldc,
+                                   void *workspace, int64_t workspace_bytes, void *stream)
+{
+    return gemm_ex<double>(kVariants, kNumVariants, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, -1,
+                       workspace, workspace_bytes);
+}
+
+extern "C" int gemm_f64_split_k_plan(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu,
+                                     int64_t workspace_bytes, int *variant, int *splits, int *k_chunk)
+{
+    if ((transa != 0 && transa != 1) || (transb != 0 && transb != 1) || M < 0 || N < 0 || K < 0 || workspace_bytes < 0)
+        return GEMM_F64_ERR_DIM;
+    if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
+    const Plan plan = plan_split_k(kVariants, kNumVariants, transa, transb, M, N, K, num_cu, (int)sizeof(double), workspace_bytes);
+    if (variant) *variant = plan.variant;
+    if (splits) *splits = plan.splits;
+    if (k_chunk) *k_chunk = plan.k_chunk;
+    return GEMM_F64_OK;
+}
+
+extern "C" int64_t gemm_f64_split_k_workspace_bytes(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu)
+{
+    int splits = 1;
+    if (gemm_f64_split_k_plan(transa, transb, M, N, K, num_cu, INT64_MAX, nullptr, &splits, nullptr) != GEMM_F64_OK) return 0;
+    return splits > 1 ? (int64_t)splits * M * N * (int64_t)sizeof(double) : 0;
+}

@@ -55,28 +55,71 @@ inline bool variant_available(const Variant &v, int transa, int transb)
 // be shorter than the time one tile needs on its own (the MFMA chain of one wave plus a fixed start-up
 // and write-back cost): that floor is what counts when there are fewer tiles than compute units.
 // Variant 0 (untiled) is never chosen.
+inline double variant_cost(const Variant &var, int64_t M, int64_t N, int64_t K, int64_t slices, int num_cu)
+{
+    const double ksteps = (double)ceil_div(K, 4);
+    const int64_t tiles = ceil_div(M, var.bm) * ceil_div(N, var.bn) * slices;
+    const int64_t per_cu = ceil_div(tiles, num_cu);
+    const double eff = var.efficiency * few_resident_penalty(per_cu < var.resident ? (int)per_cu : var.resident, var.resident);
+    const double wave_chain = (double)(var.bm / 32) * (var.bn / 32);   // MFMAs per k-step in one wave
+    const double throughput = (double)per_cu * (wave_chain * ksteps / eff + var.overhead);
+    const double floor_alone = wave_chain * ksteps + kLoneTileSlots;
+    return throughput > floor_alone ? throughput : floor_alone;
+}
+
 inline int choose_variant(const Variant *variants, int count, int transa, int transb, int64_t M, int64_t N, int64_t K,
-                          int num_cu)
+                          int num_cu, int64_t slices = 1, double *cost_out = nullptr)
 {
     if (num_cu < 1) num_cu = 1;
-    if (M <= 0 || N <= 0) return 1;
     if (K < 1) K = 1;
-    const double ksteps = (double)ceil_div(K, 4);
     int best = 1;
     double best_cost = 0.0;
-    for (int v = 1; v < count; ++v) {
-        const Variant &var = variants[v];
-        if (!variant_available(var, transa, transb)) continue;
-        const int64_t tiles = ceil_div(M, var.bm) * ceil_div(N, var.bn);
-        const int64_t per_cu = ceil_div(tiles, num_cu);
-        const double eff = var.efficiency * few_resident_penalty(per_cu < var.resident ? (int)per_cu : var.resident, var.resident);
-        const double wave_chain = (double)(var.bm / 32) * (var.bn / 32);   // MFMAs per k-step in one wave
-        const double throughput = (double)per_cu * (wave_chain * ksteps / eff + var.overhead);
-        const double floor_alone = wave_chain * ksteps + kLoneTileSlots;
-        const double cost = throughput > floor_alone ? throughput : floor_alone;
-        if (v == 1 || cost < best_cost) {
-            best = v;
+    if (M > 0 && N > 0)
+        for (int v = 1; v < count; ++v) {
+            if (!variant_available(variants[v], transa, transb)) continue;
+            const double cost = variant_cost(variants[v], M, N, K, slices, num_cu);
+            if (v == 1 || cost < best_cost) {
+                best = v;
+                best_cost = cost;
+            }
+        }
+    if (cost_out) *cost_out = best_cost;
+    return best;
+}
+
+// Split K.  A problem of few tiles and a long k range leaves most compute units idle while each tile
+// walks its whole range; cutting the range into S slices gives S times as many workgroups of a S-th of
+// the length, at the price of S output slabs in a workspace and a second, memory-bound step that adds
+// them up (in a fixed order: the result does not depend on scheduling).  The plan is a pure function
+// of the shape, the CU count and the workspace on offer: for each S the cost of the first step by the
+// model above, plus the second step as (S + 2) M N elements moved at about 2.5 TB/s and a launch of 4 us,
+// converted to the model's unit; splitting must win by 10 % to be chosen.
+struct Plan {
+    int variant;
+    int splits;     // 1: no split
+    int k_chunk;    // slice length, a multiple of the stage depth (K itself when splits == 1)
+};
+
+inline Plan plan_split_k(const Variant *variants, int count, int transa, int transb, int64_t M, int64_t N, int64_t K,
+                         int num_cu, int elem_bytes, int64_t workspace_bytes)
+{
+    double base_cost = 0.0;
+    Plan best{choose_variant(variants, count, transa, transb, M, N, K, num_cu, 1, &base_cost), 1, (int)K};
+    if (M <= 0 || N <= 0 || K <= 0) return best;
+    const int bk = 8 * (16 / elem_bytes);
+    const double slot_seconds = (elem_bytes == 8 ? 64.0 : 32.0) / 2.4e9;
+    double best_cost = base_cost * 0.9;
+    static const int candidates[] = {2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32};
+    for (int s : candidates) {
+        const int64_t chunk = ceil_div(ceil_div(K, s), bk) * bk;
+        const int64_t slices = ceil_div(K, chunk);
+        if (slices < 2 || slices * M * N * elem_bytes > workspace_bytes) continue;
+        double cost = 0.0;
+        const int v = choose_variant(variants, count, transa, transb, M, N, chunk, num_cu, slices, &cost);
+        cost += ((double)(slices + 2) * M * N * elem_bytes / 2.5e12 + 4e-6) / slot_seconds;
+        if (cost < best_cost) {
             best_cost = cost;
+            best = Plan{v, (int)slices, (int)chunk};
         }
     }
     return best;
@@ -117,49 +160,77 @@ bool async_copies_possible(int64_t lda, int64_t ldb)
     return lda < limit && ldb < limit;
 }
 
+// One product to launch: the operands as the caller stores them, and how the k range is sliced.
+template <typename T>
+struct Job {
+    int transa, transb;
+    int M, N, K;
+    T alpha;
+    const T *A;
+    int64_t lda;
+    const T *B;
+    int64_t ldb;
+    T beta;
+    T *C;
+    int64_t ldc;
+    hipStream_t stream;
+    int slices;     // grid height
+    SplitK split;
+};
+
 template <typename T, int BM, int BN, int WM, int WN, bool TA, bool TB>
-hipError_t launch_mfma_t(int M, int N, int K, T alpha, const T *A, int64_t lda, const T *B, int64_t ldb, T beta, T *C,
-                         int64_t ldc, hipStream_t stream)
+hipError_t launch_mfma_t(const Job<T> &j)
 {
     constexpr int BK = 8 * (16 / (int)sizeof(T));
-    const int tiles_m = (int)ceil_div(M, BM), tiles_n = (int)ceil_div(N, BN);
-    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n)), block(kThreads);
-    const bool vec = async_copies_possible<T>(lda, ldb);
-    // The lean kernel assumes full tiles everywhere and whole K stages.
-    const bool lean = vec && (M % BM == 0) && (N % BN == 0) && (K % BK == 0);
+    const int tiles_m = (int)ceil_div(j.M, BM), tiles_n = (int)ceil_div(j.N, BN);
+    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n), (unsigned)j.slices), block(kThreads);
+    const bool vec = async_copies_possible<T>(j.lda, j.ldb);
+    // The lean kernel assumes full tiles everywhere and whole K stages (in every slice).
+    const bool lean = vec && (j.M % BM == 0) && (j.N % BN == 0) && (j.K % BK == 0) && (j.split.k_chunk % BK == 0);
     if (lean)
-        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kLean, TA, TB>), grid, block, 0, stream, M, N, K, alpha, A,
-                           lda, B, ldb, beta, C, ldc, tiles_m, tiles_n);
+        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kLean, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
+                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, tiles_m, tiles_n, j.split);
     else if (vec)
-        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kGeneric, TA, TB>), grid, block, 0, stream, M, N, K, alpha,
-                           A, lda, B, ldb, beta, C, ldc, tiles_m, tiles_n);
+        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kGeneric, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
+                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, tiles_m, tiles_n, j.split);
     else
-        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kStaged, TA, TB>), grid, block, 0, stream, M, N, K, alpha,
-                           A, lda, B, ldb, beta, C, ldc, tiles_m, tiles_n);
+        hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kStaged, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
+                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, tiles_m, tiles_n, j.split);
     return hipGetLastError();
 }
 
 template <typename T, int BM, int BN, int WM, int WN>
-hipError_t launch_mfma(int transa, int transb, int M, int N, int K, T alpha, const T *A, int64_t lda, const T *B,
-                       int64_t ldb, T beta, T *C, int64_t ldc, hipStream_t stream)
+hipError_t launch_mfma(const Job<T> &j)
 {
-    if (!transa && !transb)
-        return launch_mfma_t<T, BM, BN, WM, WN, false, false>(M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream);
-    if (!transa && transb)
-        return launch_mfma_t<T, BM, BN, WM, WN, false, true>(M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream);
-    if (transa && !transb)
-        return launch_mfma_t<T, BM, BN, WM, WN, true, false>(M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream);
-    return launch_mfma_t<T, BM, BN, WM, WN, true, true>(M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream);
+    if (!j.transa && !j.transb) return launch_mfma_t<T, BM, BN, WM, WN, false, false>(j);
+    if (!j.transa && j.transb) return launch_mfma_t<T, BM, BN, WM, WN, false, true>(j);
+    if (j.transa && !j.transb) return launch_mfma_t<T, BM, BN, WM, WN, true, false>(j);
+    return launch_mfma_t<T, BM, BN, WM, WN, true, true>(j);
 }
 
 template <typename T>
-hipError_t launch_naive(int transa, int transb, int M, int N, int K, T alpha, const T *A, int64_t lda, const T *B,
-                        int64_t ldb, T beta, T *C, int64_t ldc, hipStream_t stream)
+hipError_t launch_variant(int variant, const Job<T> &j)
 {
-    const int64_t total = (int64_t)M * N;
+    switch (variant) {
+    case 1: return launch_mfma<T, 128, 128, 2, 2>(j);
+    case 2: return launch_mfma<T, 64, 64, 2, 2>(j);
+    case 3: return launch_mfma<T, 128, 64, 2, 2>(j);
+    case 4: return launch_mfma<T, 64, 128, 2, 2>(j);
+    case 5:  // 32-row tiles: A must be k-contiguous
+        return j.transb ? launch_mfma_t<T, 32, 64, 2, 2, false, true>(j) : launch_mfma_t<T, 32, 64, 2, 2, false, false>(j);
+    case 6:  // 32-column tiles: B must be k-contiguous
+        return j.transa ? launch_mfma_t<T, 64, 32, 2, 2, true, true>(j) : launch_mfma_t<T, 64, 32, 2, 2, false, true>(j);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+template <typename T>
+hipError_t launch_naive(const Job<T> &j)
+{
+    const int64_t total = (int64_t)j.M * j.N;
     const dim3 grid((unsigned)ceil_div(total, 256)), block(256);
-    hipLaunchKernelGGL(gemm_naive_kernel<T>, grid, block, 0, stream, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta,
-                       C, ldc);
+    hipLaunchKernelGGL(gemm_naive_kernel<T>, grid, block, 0, j.stream, j.transa, j.transb, j.M, j.N, j.K, j.alpha, j.A, j.lda,
+                       j.B, j.ldb, j.beta, j.C, j.ldc);
     return hipGetLastError();
 }
 
@@ -184,14 +255,18 @@ inline int current_cu_count()
 // The body common to all entry points: C <- alpha * op(A) op(B) + beta * C.
 //   alpha == 0 or K == 0: A and B are not read; C is scaled by beta (untouched when beta == 1).
 //   beta == 0: C is not read.
+// With a workspace (device memory, may be null) and variant == -1 the k range may be split, see plan_split_k.
 template <typename T>
 int gemm_ex(const Variant *variants, int count, int transa, int transb, int64_t M, int64_t N, int64_t K, T alpha,
-            const T *A, int64_t lda, const T *B, int64_t ldb, T beta, T *C, int64_t ldc, void *stream_, int variant)
+            const T *A, int64_t lda, const T *B, int64_t ldb, T beta, T *C, int64_t ldc, void *stream_, int variant,
+            void *workspace = nullptr, int64_t workspace_bytes = 0)
 {
     const bool product = (alpha != T(0)) && K != 0;
     const int rc = validate(transa, transb, M, N, K, product, A, lda, B, ldb, C, ldc);
     if (rc != GEMM_F64_OK) return rc;
     if (variant < -1 || variant >= count) return GEMM_F64_ERR_VARIANT;
+    if (workspace_bytes < 0 || (workspace_bytes > 0 && workspace == nullptr)) return GEMM_F64_ERR_NULL;
+    if (workspace && ((uintptr_t)workspace & (sizeof(T) - 1))) return GEMM_F64_ERR_ALIGN;
     if (M == 0 || N == 0) return GEMM_F64_OK;
     if (ceil_div(M * N, 256) > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
     hipStream_t stream = (hipStream_t)stream_;
@@ -202,24 +277,32 @@ int gemm_ex(const Variant *variants, int count, int transa, int transb, int64_t 
         err = launch_scale<T>(m, n, beta, C, ldc, stream);
         return err == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
     }
-    if (variant == -1) variant = choose_variant(variants, count, transa, transb, M, N, K, current_cu_count());
-    else if (variant > 0 && !variant_available(variants[variant], transa, transb)) return GEMM_F64_ERR_VARIANT;
-    switch (variant) {
-    case 0: err = launch_naive<T>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
-    case 1: err = launch_mfma<T, 128, 128, 2, 2>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
-    case 2: err = launch_mfma<T, 64, 64, 2, 2>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
-    case 3: err = launch_mfma<T, 128, 64, 2, 2>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
-    case 4: err = launch_mfma<T, 64, 128, 2, 2>(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream); break;
-    case 5:  // 32-row tiles: A must be k-contiguous
-        err = transb ? launch_mfma_t<T, 32, 64, 2, 2, false, true>(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream)
-                     : launch_mfma_t<T, 32, 64, 2, 2, false, false>(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream);
-        break;
-    case 6:  // 32-column tiles: B must be k-contiguous
-        err = transa ? launch_mfma_t<T, 64, 32, 2, 2, true, true>(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream)
-                     : launch_mfma_t<T, 64, 32, 2, 2, false, true>(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream);
-        break;
-    default: return GEMM_F64_ERR_VARIANT;
+    Job<T> job{transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream, 1, SplitK{k, 0, 0, 0}};
+    if (variant == -1) {
+        const Plan plan = plan_split_k(variants, count, transa, transb, M, N, K, current_cu_count(), (int)sizeof(T),
+                                       workspace ? workspace_bytes : 0);
+        variant = plan.variant;
+        if (plan.splits > 1) {
+            // first step: slice y of the k range into slab y of the workspace (dense M x N), nothing scaled yet
+            T *slabs = static_cast<T *>(workspace);
+            job.alpha = T(1);
+            job.beta = T(0);
+            job.C = slabs;
+            job.ldc = N;
+            job.slices = plan.splits;
+            job.split = SplitK{plan.k_chunk, transa ? (int64_t)plan.k_chunk * lda : (int64_t)plan.k_chunk,
+                               transb ? (int64_t)plan.k_chunk : (int64_t)plan.k_chunk * ldb, M * N};
+            err = launch_variant<T>(variant, job);
+            if (err != hipSuccess) return GEMM_F64_ERR_LAUNCH;
+            // second step: C <- alpha * (sum of the slabs, in order) + beta * C
+            const dim3 grid((unsigned)ceil_div(M * N, 256)), block(256);
+            hipLaunchKernelGGL(split_k_reduce_kernel<T>, grid, block, 0, stream, m, n, plan.splits, alpha, slabs, beta, C, ldc);
+            return hipGetLastError() == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
+        }
+    } else if (variant > 0 && !variant_available(variants[variant], transa, transb)) {
+        return GEMM_F64_ERR_VARIANT;
     }
+    err = variant == 0 ? launch_naive<T>(job) : launch_variant<T>(variant, job);
     return err == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
 }
 

@@ -64,6 +64,14 @@ template <> struct Elem<float> {
     static constexpr __device__ __forceinline__ int d_row(int r, int lg) { return 4 * lg + r; }
 };
 
+// Split K: a launch of grid height S computes S consecutive slices of the k range, slice y into its own
+// output slab, to be summed afterwards.  k_chunk is the slice length (a multiple of the stage depth, or K
+// itself when nothing is split); the steps are what slice y adds, in elements, to the three base pointers.
+struct SplitK {
+    int k_chunk;
+    int64_t step_a, step_b, step_c;
+};
+
 // Workgroup id -> tile coordinates.  Block b runs on XCD b % kXcds.  Each XCD receives a
 // contiguous run of the "grouped" tile order (kGroupM tile rows at a time, column by column
 // inside a group), so the workgroups resident on one XCD at any moment form a compact patch of C
@@ -351,9 +359,15 @@ struct Panel {
 // tiles: it then schedules the K loop differently; the smaller tiles fit more waves anyway.)
 template <typename T, int BM, int BN, int WM, int WN, int MODE, bool TA, bool TB>
 __global__ void __launch_bounds__(kThreads, 2)
-gemm_mfma_kernel(int M, int N, int K, T alpha, const T *__restrict__ A, int64_t lda, const T *__restrict__ B,
-                 int64_t ldb, T beta, T *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n)
+gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, int64_t lda, const T *__restrict__ B_,
+                 int64_t ldb, T beta, T *__restrict__ C_, int64_t ldc, int tiles_m, int tiles_n, SplitK split)
 {
+    // this workgroup's slice of k (all of it when the grid has height 1)
+    const int slice = blockIdx.y;
+    const int K = min(split.k_chunk, K_total - slice * split.k_chunk);
+    const T *__restrict__ A = A_ + slice * split.step_a;
+    const T *__restrict__ B = B_ + slice * split.step_b;
+    T *__restrict__ C = C_ + slice * split.step_c;
     typedef Elem<T> EL;
     typedef typename EL::cell_t cell_t;
     typedef typename EL::acc_t acc_t;
@@ -607,6 +621,23 @@ __global__ void __launch_bounds__(256) scale_c_kernel(int M, int N, T beta, T *_
     const int i = (int)(idx / N), j = (int)(idx % N);
     T *p = C + (int64_t)i * ldc + j;
     *p = (beta != T(0)) ? beta * *p : T(0);
+}
+
+// The second step of a split K: C <- alpha * (W_0 + W_1 + ... + W_{S-1}) + beta * C, the slabs W_p (M x N, dense)
+// added in ascending p, so that the result does not depend on how the first step was scheduled.
+template <typename T>
+__global__ void __launch_bounds__(256)
+split_k_reduce_kernel(int M, int N, int splits, T alpha, const T *__restrict__ W, T beta, T *__restrict__ C, int64_t ldc)
+{
+    const int64_t total = (int64_t)M * N;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    T s = W[idx];
+    for (int p = 1; p < splits; ++p) s += W[p * total + idx];
+    const int i = (int)(idx / N), j = (int)(idx % N);
+    const bool read_c = beta != T(0);
+    const T c = read_c ? C[(int64_t)i * ldc + j] : T(0);
+    C[(int64_t)i * ldc + j] = scaled_update(alpha, s, beta, c, read_c);
 }
 
 }  // namespace gemm_detail

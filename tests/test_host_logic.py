@@ -25,7 +25,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(binding.LIB_PATH)
     names = declared_functions()
-    assert "gemm_f64" in names and "gemm_f64_ex" in names and "gemm_f32" in names and len(names) >= 19
+    assert "gemm_f64" in names and "gemm_f64_ex" in names and "gemm_f32" in names and len(names) >= 27
     for n in names:
         assert hasattr(lib, n), "libgemm_f64.so does not export " + n
     for n in names:
@@ -169,6 +169,52 @@ def test_general_entry_points_validate_transposed_shapes_and_folded_operands():
         assert ok(1, 1, 2, 3, 0, 2.0, None, 2, None, 1, 1.0, p, 3) == 0
         assert ok(0, 0, 2, 3, 4, 0.0, None, 4, None, 3, 1.0, None, 3) == -5
         assert ok(0, 0, 0, 3, 4, 1.0, None, 4, None, 3, 0.0, None, 3) == 0
+
+
+def test_split_k_plan_is_a_consistent_pure_function():
+    for plan, stage, nm in ((binding.gemm_f64_split_k_plan, 16, binding.gemm_f64_variant_name),
+                            (binding.gemm_f32_split_k_plan, 32, binding.gemm_f32_variant_name)):
+        for (M, N, K) in [(640, 640, 8192), (512, 512, 4096), (128, 128, 65536), (64, 64, 1000003), (100, 70, 5001),
+                          (256, 256, 256), (2048, 2048, 2048), (8192, 8192, 8192), (2088, 2049, 2047), (1, 1, 1), (0, 5, 7)]:
+            for ta in (0, 1):
+                for tb in (0, 1):
+                    v, splits, chunk = plan(ta, tb, M, N, K)
+                    assert plan(ta, tb, M, N, K) == (v, splits, chunk)
+                    assert splits >= 1 and nm(v) is not None and nm(v) != "naive"
+                    assert not (nm(v).startswith("mfma_32x") and ta) and not ("x32x" in nm(v) and not tb)
+                    if splits == 1:
+                        assert chunk == K
+                    else:
+                        assert chunk % stage == 0 and (splits - 1) * chunk < K <= splits * chunk
+    # few tiles and a long k range are split; the benchmark configurations are not
+    assert binding.gemm_f64_split_k_plan(0, 0, 640, 640, 8192)[1] > 1
+    assert binding.gemm_f64_split_k_plan(0, 0, 128, 128, 65536)[1] > 1
+    for (M, N, K) in [(256, 256, 256), (2048, 2048, 2048), (2088, 2049, 2047), (8192, 8192, 8192), (16384, 16384, 256)]:
+        assert binding.gemm_f64_split_k_plan(0, 0, M, N, K)[1] == 1
+        assert binding.gemm_f64_split_k_workspace_bytes(0, 0, M, N, K) == 0
+    # the workspace on offer bounds the number of slabs; none at all means no split
+    M, N, K = 640, 640, 8192
+    want = binding.gemm_f64_split_k_workspace_bytes(0, 0, M, N, K)
+    v, splits, chunk = binding.gemm_f64_split_k_plan(0, 0, M, N, K)
+    assert want == splits * M * N * 8
+    for ws in (0, M * N * 8, 2 * M * N * 8, 3 * M * N * 8 + 7, want - 1, want):
+        s2 = binding.gemm_f64_split_k_plan(0, 0, M, N, K, workspace_bytes=ws)[1]
+        assert s2 * M * N * 8 <= ws or s2 == 1
+    assert binding.gemm_f64_split_k_plan(0, 0, M, N, K, workspace_bytes=0)[1] == 1
+    assert binding.load().gemm_f64_split_k_plan(2, 0, 8, 8, 8, 256, 0, None, None, None) == -1
+    assert binding.load().gemm_f64_split_k_plan(0, 0, -1, 8, 8, 256, 0, None, None, None) == -1
+
+
+def test_workspace_arguments_are_validated_before_any_launch():
+    p = 0x1000
+    raw = binding.load().gemm_f64_general_ws
+    # an empty output (M = 0) passes the operand checks with null operands, which isolates the workspace checks
+    empty = lambda ws, nbytes: raw(0, 0, 0, 3, 4, 1.0, None, 4, None, 3, 1.0, None, 3, ws, nbytes, None)
+    assert empty(None, 0) == 0
+    assert empty(None, 64) == -5          # bytes on offer but no pointer
+    assert empty(p + 4, 64) == -6         # not aligned to the element
+    assert empty(p, -1) == -5
+    assert empty(p, 64) == 0
 
 
 def test_gflops_convention_matches_the_papers_printed_numbers():
