@@ -155,3 +155,36 @@ def test_mfma_probe_runs_and_validates_its_arguments(gpu_device):
 
 def load_raw():
     return binding.load()
+
+
+def test_large_ragged_shapes_match_the_exact_integer_product_everywhere(gpu_device):
+    # sizes the CPU oracle cannot do whole: on integer data every correct GEMM is exact, so the product computed
+    # on the device by the vendor library serves as a full-coverage cross-check (secondary: the oracle-based
+    # tests are the bar); complete sampled rows still go through the oracle
+    rng = np.random.default_rng(7)
+    for case in range(10):
+        M, N, K = (int(rng.integers(1500, 5000)) for _ in range(3))
+        ta, tb = int(rng.integers(2)), int(rng.integers(2))
+        alpha, beta = float(rng.choice([1.0, -2.0, 3.0])), float(rng.choice([0.0, 1.0, -1.0]))
+        g = torch.Generator(device=DEV)
+        g.manual_seed(1000 + case)
+        A = torch.randint(-4, 5, (M, K), generator=g, device=DEV).double()
+        B = torch.randint(-4, 5, (K, N), generator=g, device=DEV).double()
+        C0 = torch.randint(-4, 5, (M, N), generator=g, device=DEV).double()
+        lda, ldb, ldc = (M if ta else K) + int(rng.integers(0, 4)), (K if tb else N) + int(rng.integers(0, 4)), N + int(rng.integers(0, 4))
+        dA = torch.full((K if ta else M, lda), float("nan"), dtype=torch.float64, device=DEV)
+        dB = torch.full((N if tb else K, ldb), float("nan"), dtype=torch.float64, device=DEV)
+        dC = torch.full((M, ldc), float("nan"), dtype=torch.float64, device=DEV)
+        dA[:, :(M if ta else K)] = A.t() if ta else A
+        dB[:, :(K if tb else N)] = B.t() if tb else B
+        dC[:, :N] = C0
+        binding.gemm_f64_general(ta, tb, M, N, K, alpha, dA, lda, dB, ldb, beta, dC, ldc)
+        torch.cuda.synchronize()
+        what = "case %d: %s trans %s alpha %g beta %g" % (case, (M, N, K), (ta, tb), alpha, beta)
+        assert torch.equal(dC[:, :N], alpha * (A @ B) + beta * C0), what
+        assert bool(torch.isnan(dC[:, N:]).all()), what + ": C padding written"
+        rows = synth.sample_rows(M, 24, seed=case)
+        Ar = np.ascontiguousarray(A[torch.from_numpy(rows).to(DEV)].cpu().numpy())
+        want = np.ascontiguousarray(C0[torch.from_numpy(rows).to(DEV)].cpu().numpy())
+        oracle.gemm_general_ref(0, 0, alpha, Ar, B.cpu().numpy(), beta, want)
+        pins.assert_bitwise(dC[torch.from_numpy(rows).to(DEV)][:, :N].cpu().numpy(), want, what + " (oracle rows)")
