@@ -11,6 +11,7 @@ done for the single-precision path (gemm_f32, FP32 MFMA peak 157.3 TFLOP/s, floa
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3_8192] [--variant -1] [--dtype f64|f32]
     python bench.py --copy-calibration     # plain device copy of known size, for scaling rocprof counters
     python bench.py --compare-vendor       # adds the vendor BLAS (torch.addmm) timed on the same buffers, as context
+    python bench.py --workload c1_2048 --cold-cache   # adds the same call rotated over > 1 GiB of distinct operand sets
 """
 import argparse
 import json
@@ -64,9 +65,18 @@ def cpu_baseline(w, seed, target_seconds=12.0, np_dtype=None):
     rows = max(pilot_rows, min(w.M, (rows // threads) * threads))
     t = run(rows)
     gflops = 2.0 * rows * w.N * w.K / t / 1e9
+    # the paper's own numbers are single-core (Section 1.3): the same oracle on one thread, for about three seconds
+    rows1 = max(1, min(w.M, int(3.0 * rows / t / threads)))
+    oracle.set_ref_threads(1)
+    try:
+        t1 = run(rows1)
+    finally:
+        oracle.set_ref_threads(threads)
     return {"value": round(gflops, 3), "unit": "GFLOP/s", "cores": threads, "kind": "oracle",
             "sample": "first %d of %d rows of %s (N=%d, K=%d) in %.2f s; full-size time extrapolates to %.0f s"
-                      % (rows, w.M, w.name, w.N, w.K, t, t * w.M / rows)}
+                      % (rows, w.M, w.name, w.N, w.K, t, t * w.M / rows),
+            "single_thread": {"value": round(2.0 * rows1 * w.N * w.K / t1 / 1e9, 3), "unit": "GFLOP/s", "cores": 1,
+                              "sample": "first %d rows in %.2f s" % (rows1, t1)}}
 
 
 def copy_calibration():
@@ -95,6 +105,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true")
     ap.add_argument("--compare-vendor", action="store_true",
                     help="after the measurement, time the vendor BLAS behind torch.addmm on the same buffers (context only)")
+    ap.add_argument("--cold-cache", action="store_true",
+                    help="after the measurement, time the same call rotated over distinct operand sets of more than "
+                         "1 GiB in total, so that no call finds its operands in the 256 MiB last-level cache")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -202,6 +215,31 @@ def main():
     mfma_only = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
     out["roofline"]["mfma_only_tflops"] = round(mfma_only, 2)
     out["roofline"]["frac_of_mfma_only"] = round(achieved_tflops / mfma_only, 4)
+    if args.cold_cache:
+        # Repeated calls on one operand set of a small workload are served from the last-level cache (256 MiB); here
+        # consecutive calls use different sets, more than 1 GiB in all, so every call starts from HBM.
+        set_bytes = (dA.numel() + dB.numel() + dC.numel()) * elem
+        n_sets = max(2, -(-(1 << 30) // set_bytes) + 1)
+        sets = [(dA.clone(), dB.clone(), dC.clone()) for _ in range(n_sets)]
+        calls = n_sets * max(1, min(args.steps, 200) // n_sets)
+
+        def cold_round():
+            for i in range(calls):
+                a, b, c = sets[i % n_sets]
+                gemm_ex(w.M, w.N, w.K, a, w.lda, b, w.ldb, c, w.ldc, stream=stream, variant=args.variant)
+
+        cold_round()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        cold_round()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        cms = e0.elapsed_time(e1) / calls
+        out["cold_cache"] = {"value": round(w.flops / (cms * 1e-3) / 1e9, 1), "unit": "GFLOP/s", "ms_per_call": round(cms, 4),
+                             "operand_sets": n_sets, "bytes_per_set": set_bytes, "calls": calls,
+                             "frac": round(w.flops / (cms * 1e-3) / 1e12 / peak, 4)}
+        del sets
     if args.compare_vendor:
         # Context, never the product path: the library routine behind torch.addmm (rocBLAS / hipBLASLt) on the
         # same operands, timed the same way after the measurement above is complete (dense views only).
