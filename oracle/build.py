@@ -11,7 +11,7 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SOURCES = [os.path.join(HERE, "gemm_ref.c"), os.path.join(HERE, "gemm_ref_f32.c"),
-           os.path.join(HERE, "gemm_general_ref.c")]
+           os.path.join(HERE, "gemm_general_ref.c"), os.path.join(HERE, "gemm_strided_ref.c")]
 LIB = os.path.join(HERE, "liboracle_gemm.so")
 
 FLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",

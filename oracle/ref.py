@@ -36,6 +36,12 @@ def _load():
         lib.gemm_f32_general_ref.argtypes = [ctypes.c_int, ctypes.c_int, i64, i64, i64, ctypes.c_float, dp, i64,
                                              dp, i64, ctypes.c_float, dp, i64]
         lib.gemm_f32_general_ref.restype = ctypes.c_int
+        lib.gemm_f64_strided_ref.argtypes = [i64, i64, i64, ctypes.c_double, dp, i64, i64, dp, i64, i64,
+                                             ctypes.c_double, dp, i64, i64]
+        lib.gemm_f64_strided_ref.restype = ctypes.c_int
+        lib.gemm_f32_strided_ref.argtypes = [i64, i64, i64, ctypes.c_float, dp, i64, i64, dp, i64, i64,
+                                             ctypes.c_float, dp, i64, i64]
+        lib.gemm_f32_strided_ref.restype = ctypes.c_int
         lib.gemm_f64_ref_threads.restype = ctypes.c_int
         lib.gemm_f64_ref_set_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -130,6 +136,38 @@ def general_scale(transa, transb, alpha, A, B, beta, C0):
         S = np.zeros(C0.shape, dtype=np.float64)  # C0 is not read then and may hold NaN
     return gemm_general_ref(transa, transb, abs(float(alpha)), np.abs(A.astype(np.float64)),
                             np.abs(B.astype(np.float64)), abs(float(beta)), np.ascontiguousarray(S))
+
+
+def element_strides(x: np.ndarray):
+    """(row stride, column stride) of a 2-D view in elements; an axis of extent 0 or 1 reports 1."""
+    assert x.ndim == 2
+    sz = x.dtype.itemsize
+    out = []
+    for axis in (0, 1):
+        if x.shape[axis] > 1 and x.size:
+            assert x.strides[axis] > 0 and x.strides[axis] % sz == 0, "strides must be positive element multiples"
+            out.append(x.strides[axis] // sz)
+        else:
+            out.append(1)
+    return tuple(out)
+
+
+def gemm_strided_ref(alpha, A, B, beta, C):
+    """C <- alpha * A @ B + beta * C in place for 2-D views with any positive strides (oracle/gemm_strided_ref.c):
+    row-major, column-major (a transposed view), or regularly sampled sub-matrices of either.  Returns C."""
+    f32 = C.dtype == np.float32
+    want = np.float32 if f32 else np.float64
+    assert A.dtype == want and B.dtype == want and C.dtype == want and C.flags.writeable
+    M, N = C.shape
+    K = A.shape[1]
+    assert A.shape == (M, K) and B.shape == (K, N)
+    (rsa, csa), (rsb, csb), (rsc, csc) = element_strides(A), element_strides(B), element_strides(C)
+    fn = getattr(_load(), "gemm_f32_strided_ref" if f32 else "gemm_f64_strided_ref")
+    rc = fn(M, N, K, float(want(alpha)), A.ctypes.data, rsa, csa, B.ctypes.data, rsb, csb, float(want(beta)),
+            C.ctypes.data, rsc, csc)
+    if rc != 0:
+        raise ValueError("gemm_strided_ref failed with code %d" % rc)
+    return C
 
 
 def raw(name):
