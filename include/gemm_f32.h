@@ -61,6 +61,14 @@ int gemm_f32_general_ex(int transa, int transb, int64_t M, int64_t N, int64_t K,
                         float beta, float *C, int64_t ldc,
                         void *stream, int variant);
 
+/* The float counterpart of gemm_f64_strided (operands addressed through a row and a column stride each, Section 2.9
+ * and Section 2.15 Q4 of the paper; pointers 4-byte aligned; tolerance of gemm_f32_general). */
+int gemm_f32_strided(int64_t M, int64_t N, int64_t K,
+                     float alpha, const float *A, int64_t rsa, int64_t csa,
+                     const float *B, int64_t rsb, int64_t csb,
+                     float beta, float *C, int64_t rsc, int64_t csc,
+                     void *stream);
+
 /* The float counterparts of gemm_f64_general_ws, gemm_f64_split_k_plan and gemm_f64_split_k_workspace_bytes
  * (workspace 4-byte aligned, slice lengths multiples of 32). */
 int gemm_f32_general_ws(int transa, int transb, int64_t M, int64_t N, int64_t K,

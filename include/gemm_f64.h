@@ -138,6 +138,39 @@ int gemm_f64_general_ex(int transa, int transb, int64_t M, int64_t N, int64_t K,
                         void *stream, int variant);
 
 /*
+ * gemm_f64_strided: C <- alpha * A * B + beta * C with every operand addressed through a row stride and a column
+ * stride, in elements:
+ *
+ *     A(i,k) = A[i*rsa + k*csa]   (M x K),   B(k,j) = B[k*rsb + j*csb]   (K x N),   C(i,j) = C[i*rsc + j*csc]   (M x N).
+ *
+ * The paper describes an operand as an index space plus an affine layout map into its buffer and names a matrix
+ * with access strides 128 and 2 inside a larger buffer as an example (Section 2.9); strides and transposes of the
+ * GEMM operands are such maps (Section 2.15 Q4).  Two strides cover row-major (cs == 1), column-major or
+ * transposed (rs == 1), and every regularly sampled sub-matrix of either; callers that hold column-major data
+ * (Fortran BLAS conventions) pass rs = 1, cs = leading dimension for all three operands.
+ *
+ *   strides     all >= 1 (GEMM_F64_ERR_LDA / _LDB / _LDC names the operand otherwise); the stride of an extent of
+ *               0 or 1 is never used.  A and B are only read, so their elements may share memory (a stride smaller
+ *               than the extent it steps over is allowed).  The elements of C must be distinct and the library only
+ *               accepts layouts where that is evident: rsc >= csc*(N-1)+1, or csc >= rsc*(M-1)+1, or M <= 1 or
+ *               N <= 1; anything else is GEMM_F64_ERR_LDC.
+ *   pointers    device, 8-byte aligned, address of element (0,0); elements that the strides do not reach are never
+ *               read and never written.  Folding of alpha == 0, K == 0 and beta == 0, the arithmetic of the
+ *               scalar tail, the other error codes and the tolerance are those of gemm_f64_general.
+ *
+ * Speed: when each operand has a unit stride and its other stride covers the extent (a leading dimension), the
+ * call is gemm_f64_general on the same buffers (a column-major C is computed as the transposed problem
+ * C^T = B^T A^T, which adds the same products in the same order) and runs on the MFMA kernels.  Any other layout
+ * runs an element-wise kernel, one thread per element of C: correct, never read or written outside the layout, and
+ * orders of magnitude slower.
+ */
+int gemm_f64_strided(int64_t M, int64_t N, int64_t K,
+                     double alpha, const double *A, int64_t rsa, int64_t csa,
+                     const double *B, int64_t rsb, int64_t csb,
+                     double beta, double *C, int64_t rsc, int64_t csc,
+                     void *stream);
+
+/*
  * gemm_f64_general_ws: gemm_f64_general with a workspace on offer (the paper's Section 2.15 Q5 asks how tuning
  * choices are to be made per problem; splitting the k range is the one choice that needs memory).  For problems of
  * few output tiles and a long k range the library may cut the range into S slices, compute the S partial products

@@ -83,6 +83,10 @@ def load():
     lib.gemm_f32_general.restype = ci
     lib.gemm_f32_general_ex.argtypes = [ci, ci, i64, i64, i64, cf, vp, i64, vp, i64, cf, vp, i64, vp, ci]
     lib.gemm_f32_general_ex.restype = ci
+    lib.gemm_f64_strided.argtypes = [i64, i64, i64, cd, vp, i64, i64, vp, i64, i64, cd, vp, i64, i64, vp]
+    lib.gemm_f64_strided.restype = ci
+    lib.gemm_f32_strided.argtypes = [i64, i64, i64, cf, vp, i64, i64, vp, i64, i64, cf, vp, i64, i64, vp]
+    lib.gemm_f32_strided.restype = ci
     _lib = lib
     return lib
 
@@ -245,6 +249,25 @@ def gemm_f64_general_ws(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C,
 def gemm_f32_general_ws(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace, workspace_bytes, stream=None):
     _check(load().gemm_f32_general_ws(int(transa), int(transb), M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
                                       _ptr(C), ldc, _ptr(workspace), int(workspace_bytes), _stream(stream)))
+
+
+def gemm_f64_strided(M, N, K, alpha, A, rsa, csa, B, rsb, csb, beta, C, rsc, csc, stream=None):
+    """Enqueue C <- alpha * A @ B + beta * C (double) with X(r, c) = X[r * rs + c * cs] for every operand."""
+    _check(load().gemm_f64_strided(M, N, K, alpha, _ptr(A), rsa, csa, _ptr(B), rsb, csb, beta, _ptr(C), rsc, csc,
+                                   _stream(stream)))
+
+
+def gemm_f32_strided(M, N, K, alpha, A, rsa, csa, B, rsb, csb, beta, C, rsc, csc, stream=None):
+    _check(load().gemm_f32_strided(M, N, K, alpha, _ptr(A), rsa, csa, _ptr(B), rsb, csb, beta, _ptr(C), rsc, csc,
+                                   _stream(stream)))
+
+
+def gemm_f64_strided_raw(M, N, K, alpha, A, rsa, csa, B, rsb, csb, beta, C, rsc, csc, stream=0) -> int:
+    return int(load().gemm_f64_strided(M, N, K, alpha, _ptr(A), rsa, csa, _ptr(B), rsb, csb, beta, _ptr(C), rsc, csc, stream))
+
+
+def gemm_f32_strided_raw(M, N, K, alpha, A, rsa, csa, B, rsb, csb, beta, C, rsc, csc, stream=0) -> int:
+    return int(load().gemm_f32_strided(M, N, K, alpha, _ptr(A), rsa, csa, _ptr(B), rsb, csb, beta, _ptr(C), rsc, csc, stream))
 
 
 def _plan(fn, transa, transb, M, N, K, num_cu, workspace_bytes):

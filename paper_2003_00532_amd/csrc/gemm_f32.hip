@@ -72,6 +72,13 @@ extern "C" int gemm_f32_general_ws(int transa, int transb, int64_t M, int64_t N,
                        workspace, workspace_bytes);
 }
 
+extern "C" int gemm_f32_strided(int64_t M, int64_t N, int64_t K, float alpha, const float *A, int64_t rsa, int64_t csa,
+                                const float *B, int64_t rsb, int64_t csb, float beta, float *C, int64_t rsc, int64_t csc,
+                                void *stream)
+{
+    return gemm_strided<float>(kVariants, kNumVariants, M, N, K, alpha, A, rsa, csa, B, rsb, csb, beta, C, rsc, csc, stream);
+}
+
 extern "C" int gemm_f32_split_k_plan(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu,
                                      int64_t workspace_bytes, int *variant, int *splits, int *k_chunk)
 {

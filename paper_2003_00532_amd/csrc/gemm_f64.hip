@@ -51,9 +51,9 @@ extern "C" const char *gemm_f64_strerror(int code)
     switch (code) {
     case GEMM_F64_OK: return "success";
     case GEMM_F64_ERR_DIM: return "negative dimension, transpose flag other than 0 or 1, or index out of range";
-    case GEMM_F64_ERR_LDA: return "lda smaller than the stored row of A";
-    case GEMM_F64_ERR_LDB: return "ldb smaller than the stored row of B";
-    case GEMM_F64_ERR_LDC: return "ldc smaller than max(1, N)";
+    case GEMM_F64_ERR_LDA: return "lda smaller than the stored row of A, or a stride of A below 1";
+    case GEMM_F64_ERR_LDB: return "ldb smaller than the stored row of B, or a stride of B below 1";
+    case GEMM_F64_ERR_LDC: return "ldc smaller than max(1, N), or strides of C below 1 or under which its elements overlap";
     case GEMM_F64_ERR_NULL: return "null pointer for a non-empty operand";
     case GEMM_F64_ERR_ALIGN: return "pointer not aligned to the element size";
     case GEMM_F64_ERR_LAUNCH: return "HIP kernel launch failed";
@@ -63,7 +63,7 @@ extern "C" const char *gemm_f64_strerror(int code)
     }
 }
 
-extern "C" int gemm_f64_version(void) { return 300; }
+extern "C" int gemm_f64_version(void) { return 400; }
 
 extern "C" int gemm_f64_choose_variant_general(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu)
 {
@@ -103,6 +103,13 @@ extern "C" int gemm_f64_general_ws(int transa, int transb, int64_t M, int64_t N,
 {
     return gemm_ex<double>(kVariants, kNumVariants, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, -1,
                        workspace, workspace_bytes);
+}
+
+extern "C" int gemm_f64_strided(int64_t M, int64_t N, int64_t K, double alpha, const double *A, int64_t rsa, int64_t csa,
+                                const double *B, int64_t rsb, int64_t csb, double beta, double *C, int64_t rsc, int64_t csc,
+                                void *stream)
+{
+    return gemm_strided<double>(kVariants, kNumVariants, M, N, K, alpha, A, rsa, csa, B, rsb, csb, beta, C, rsc, csc, stream);
 }
 
 extern "C" int gemm_f64_split_k_plan(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu,

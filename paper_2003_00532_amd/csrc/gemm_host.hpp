@@ -229,17 +229,17 @@ hipError_t launch_naive(const Job<T> &j)
 {
     const int64_t total = (int64_t)j.M * j.N;
     const dim3 grid((unsigned)ceil_div(total, 256)), block(256);
-    hipLaunchKernelGGL(gemm_naive_kernel<T>, grid, block, 0, j.stream, j.transa, j.transb, j.M, j.N, j.K, j.alpha, j.A, j.lda,
-                       j.B, j.ldb, j.beta, j.C, j.ldc);
+    hipLaunchKernelGGL(gemm_naive_kernel<T>, grid, block, 0, j.stream, j.M, j.N, j.K, j.alpha, j.A, j.transa ? 1 : j.lda,
+                       j.transa ? j.lda : 1, j.B, j.transb ? 1 : j.ldb, j.transb ? j.ldb : 1, j.beta, j.C, j.ldc, (int64_t)1);
     return hipGetLastError();
 }
 
 template <typename T>
-hipError_t launch_scale(int M, int N, T beta, T *C, int64_t ldc, hipStream_t stream)
+hipError_t launch_scale(int M, int N, T beta, T *C, int64_t rsc, int64_t csc, hipStream_t stream)
 {
     const int64_t total = (int64_t)M * N;
     const dim3 grid((unsigned)ceil_div(total, 256)), block(256);
-    hipLaunchKernelGGL(scale_c_kernel<T>, grid, block, 0, stream, M, N, beta, C, ldc);
+    hipLaunchKernelGGL(scale_c_kernel<T>, grid, block, 0, stream, M, N, beta, C, rsc, csc);
     return hipGetLastError();
 }
 
@@ -274,7 +274,7 @@ int gemm_ex(const Variant *variants, int count, int transa, int transb, int64_t 
     hipError_t err = hipSuccess;
     if (!product) {
         if (beta == T(1)) return GEMM_F64_OK;
-        err = launch_scale<T>(m, n, beta, C, ldc, stream);
+        err = launch_scale<T>(m, n, beta, C, ldc, 1, stream);
         return err == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
     }
     Job<T> job{transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream, 1, SplitK{k, 0, 0, 0}};
@@ -304,6 +304,73 @@ int gemm_ex(const Variant *variants, int count, int transa, int transb, int64_t 
     }
     err = variant == 0 ? launch_naive<T>(job) : launch_variant<T>(variant, job);
     return err == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
+}
+
+// How one operand with two strides maps onto the row-major kernels.  kRows: the column stride is 1 and the row
+// stride is a leading dimension that covers the row; kColumns: the row stride is 1 and the column stride covers
+// the column (the transposed view of a row-major array); kNeither: anything else (sampled sub-matrices, rows that
+// share elements), which only the element-wise kernel handles.  An extent of 0 or 1 makes its stride irrelevant.
+enum Layout { kRows, kColumns, kNeither };
+
+inline Layout classify(int64_t rows, int64_t cols, int64_t rs, int64_t cs, int64_t *ld)
+{
+    if ((cs == 1 || cols <= 1) && (rs >= cols || rows <= 1)) {
+        *ld = rows <= 1 ? (cols > 1 ? cols : 1) : rs;
+        return kRows;
+    }
+    if ((rs == 1 || rows <= 1) && (cs >= rows || cols <= 1)) {
+        *ld = cols <= 1 ? (rows > 1 ? rows : 1) : cs;
+        return kColumns;
+    }
+    return kNeither;
+}
+
+// C <- alpha * A B + beta * C with X(r, c) = X[r * rs + c * cs] for each operand (Section 2.9: an operand is an
+// index space plus an affine layout map; Section 2.15 Q4: strides and transposes are such maps).  When every
+// operand has a unit stride the call is the transposed signature (a column-major C is the transposed problem
+// C^T = B^T A^T, which sums the same products in the same order) and runs on the tiled kernels; otherwise the
+// element-wise kernel computes it.  The elements of C must be distinct: one of its strides must span the whole
+// extent of the other.
+template <typename T>
+int gemm_strided(const Variant *variants, int count, int64_t M, int64_t N, int64_t K, T alpha, const T *A, int64_t rsa,
+                 int64_t csa, const T *B, int64_t rsb, int64_t csb, T beta, T *C, int64_t rsc, int64_t csc, void *stream_)
+{
+    if (M < 0 || N < 0 || K < 0) return GEMM_F64_ERR_DIM;
+    if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
+    if (rsa < 1 || csa < 1) return GEMM_F64_ERR_LDA;
+    if (rsb < 1 || csb < 1) return GEMM_F64_ERR_LDB;
+    if (rsc < 1 || csc < 1) return GEMM_F64_ERR_LDC;
+    if (M > 1 && N > 1) {
+        const __int128 row_span = (__int128)csc * (N - 1) + 1, col_span = (__int128)rsc * (M - 1) + 1;
+        if (!((__int128)rsc >= row_span || (__int128)csc >= col_span)) return GEMM_F64_ERR_LDC;
+    }
+    const bool product = (alpha != T(0)) && K != 0;
+    const bool c_live = M > 0 && N > 0, ab_live = c_live && product;
+    if (c_live && C == nullptr) return GEMM_F64_ERR_NULL;
+    if (ab_live && (A == nullptr || B == nullptr)) return GEMM_F64_ERR_NULL;
+    const uintptr_t mask = sizeof(T) - 1;
+    if (c_live && ((uintptr_t)C & mask)) return GEMM_F64_ERR_ALIGN;
+    if (ab_live && (((uintptr_t)A & mask) || ((uintptr_t)B & mask))) return GEMM_F64_ERR_ALIGN;
+    if (!c_live) return GEMM_F64_OK;
+    if (ceil_div(M * N, 256) > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
+
+    int64_t lda = 1, ldb = 1, ldc = 1;
+    const Layout la = classify(M, K, rsa, csa, &lda), lb = classify(K, N, rsb, csb, &ldb), lc = classify(M, N, rsc, csc, &ldc);
+    if (la != kNeither && lb != kNeither && lc != kNeither) {
+        const int ta = la == kColumns, tb = lb == kColumns;
+        if (lc == kRows) return gemm_ex<T>(variants, count, ta, tb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream_, -1);
+        // C^T (N x M, row-major with leading dimension csc) = alpha * B^T A^T + beta * C^T
+        return gemm_ex<T>(variants, count, !tb, !ta, N, M, K, alpha, B, ldb, A, lda, beta, C, ldc, stream_, -1);
+    }
+    hipStream_t stream = (hipStream_t)stream_;
+    const int m = (int)M, n = (int)N, k = (int)K;
+    if (!product) {
+        if (beta == T(1)) return GEMM_F64_OK;
+        return launch_scale<T>(m, n, beta, C, rsc, csc, stream) == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
+    }
+    const dim3 grid((unsigned)ceil_div(M * N, 256)), block(256);
+    hipLaunchKernelGGL(gemm_naive_kernel<T>, grid, block, 0, stream, m, n, k, alpha, A, rsa, csa, B, rsb, csb, beta, C, rsc, csc);
+    return hipGetLastError() == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
 }
 
 }  // namespace gemm_detail

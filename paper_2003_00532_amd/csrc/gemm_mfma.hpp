@@ -599,34 +599,35 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, i
 }
 
 // Reference-shaped kernel without tiling or staging: one thread per element of C, k ascending.
-// Kept as the bottom rung of the ladder (the paper's Section 2.3 starting point) and as an
-// on-device cross-check that shares nothing with the MFMA kernel.
+// Kept as the bottom rung of the ladder (the paper's Section 2.3 starting point), as an
+// on-device cross-check that shares nothing with the MFMA kernel, and, since every operand is
+// addressed through a row stride and a column stride (X(r, c) = X[r * rs + c * cs], the affine layout
+// maps of Section 2.9), as the path for layouts in which no stride is 1.
 template <typename T>
 __global__ void __launch_bounds__(256)
-gemm_naive_kernel(int transa, int transb, int M, int N, int K, T alpha, const T *__restrict__ A, int64_t lda,
-                  const T *__restrict__ B, int64_t ldb, T beta, T *__restrict__ C, int64_t ldc)
+gemm_naive_kernel(int M, int N, int K, T alpha, const T *__restrict__ A, int64_t rsa, int64_t csa, const T *__restrict__ B,
+                  int64_t rsb, int64_t csb, T beta, T *__restrict__ C, int64_t rsc, int64_t csc)
 {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (int64_t)M * N) return;
     const int i = (int)(idx / N), j = (int)(idx % N);
-    const int64_t a_i = transa ? 1 : lda, a_k = transa ? lda : 1, b_k = transb ? 1 : ldb, b_j = transb ? ldb : 1;
-    const T *a = A + (int64_t)i * a_i, *b = B + (int64_t)j * b_j;
+    const T *a = A + (int64_t)i * rsa, *b = B + (int64_t)j * csb;
     T acc = T(0);
-    for (int k = 0; k < K; ++k) acc += a[k * a_k] * b[k * b_k];
+    for (int k = 0; k < K; ++k) acc += a[k * csa] * b[k * rsb];
     const bool read_c = beta != T(0);
-    const T c = read_c ? C[(int64_t)i * ldc + j] : T(0);
-    C[(int64_t)i * ldc + j] = scaled_update(alpha, acc, beta, c, read_c);
+    T *c = C + (int64_t)i * rsc + (int64_t)j * csc;
+    *c = scaled_update(alpha, acc, beta, read_c ? *c : T(0), read_c);
 }
 
 // C <- beta * C (all zeros when beta is zero, whatever C held): what is left of the operation when
 // alpha is zero or K is zero.
 template <typename T>
-__global__ void __launch_bounds__(256) scale_c_kernel(int M, int N, T beta, T *__restrict__ C, int64_t ldc)
+__global__ void __launch_bounds__(256) scale_c_kernel(int M, int N, T beta, T *__restrict__ C, int64_t rsc, int64_t csc)
 {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (int64_t)M * N) return;
     const int i = (int)(idx / N), j = (int)(idx % N);
-    T *p = C + (int64_t)i * ldc + j;
+    T *p = C + (int64_t)i * rsc + (int64_t)j * csc;
     *p = (beta != T(0)) ? beta * *p : T(0);
 }
 

@@ -26,6 +26,8 @@ int main(void)
     if (gemm_f32_general(0, 3, 2, 2, 2, 1.0f, (const float *)fake, 2, (const float *)fake, 2, 1.0f, (float *)fake, 2, NULL) != GEMM_F64_ERR_DIM)
         return 11;
     if (gemm_f64_general_ws(0, 0, 0, 2, 2, 1.0, NULL, 2, NULL, 2, 1.0, NULL, 2, NULL, 8, NULL) != GEMM_F64_ERR_NULL) return 12;
+    if (gemm_f64_strided(2, 3, 4, 1.0, fake, 4, 1, fake, 3, 1, 1.0, fake, 2, 1, NULL) != GEMM_F64_ERR_LDC) return 13;
+    if (gemm_f32_strided(2, 3, 4, 0.0f, NULL, 1, 2, NULL, 1, 4, 1.0f, (float *)fake, 1, 2, NULL) != GEMM_F64_OK) return 14;
     puts("c abi client ok");
     return 0;
 }

@@ -171,6 +171,34 @@ def test_general_entry_points_validate_transposed_shapes_and_folded_operands():
         assert ok(0, 0, 0, 3, 4, 1.0, None, 4, None, 3, 0.0, None, 3) == 0
 
 
+def test_strided_entry_points_validate_strides_before_any_launch():
+    p = 0x1000
+    for raw, off in ((binding.gemm_f64_strided_raw, 4), (binding.gemm_f32_strided_raw, 2)):
+        # (M, N, K, alpha, A, rsa, csa, B, rsb, csb, beta, C, rsc, csc); alpha == 0 with beta == 1 passes validation
+        # and launches nothing, so an accepted layout shows up as 0 without a GPU
+        def call(M=2, N=3, K=4, alpha=0.0, a=p, sa=(4, 1), b=p, sb=(3, 1), beta=1.0, c=p, sc=(3, 1)):
+            return raw(M, N, K, alpha, a, sa[0], sa[1], b, sb[0], sb[1], beta, c, sc[0], sc[1])
+        assert call() == 0
+        assert call(M=-1) == -1 and call(N=-1) == -1 and call(K=-1) == -1
+        assert call(M=2 ** 31) == -8
+        assert call(sa=(0, 1)) == -2 and call(sa=(4, 0)) == -2 and call(sa=(-1, 1)) == -2
+        assert call(sb=(0, 1)) == -3 and call(sb=(3, -2)) == -3
+        assert call(sc=(0, 1)) == -4 and call(sc=(3, 0)) == -4
+        assert call(sa=(1, 1)) == 0 and call(sb=(1, 1)) == 0            # read-only operands may overlap themselves
+        assert call(sc=(2, 1)) == -4 and call(sc=(1, 1)) == -4          # C may not
+        assert call(sc=(1, 2)) == 0                                     # column-major C: csc >= M
+        assert call(sc=(4, 2)) == -4 and call(sc=(5, 2)) == 0           # sampled rows: rsc >= csc * (N - 1) + 1
+        assert call(sc=(3, 2)) == -4 and call(sc=(3, 3)) == -4 and call(sc=(3, 4)) == 0   # csc >= rsc * (M - 1) + 1
+        assert call(M=1, sc=(1, 1)) == 0 and call(N=1, sc=(1, 1)) == 0  # a single row or column is always distinct
+        assert call(sc=(2 ** 62, 2 ** 60)) == 0 and call(sc=(2 ** 61, 2 ** 61)) == -4     # no overflow in the check
+        assert call(c=None) == -5 and call(c=p + off) == -6
+        assert call(a=None, b=None) == 0                                # alpha == 0: A and B are not needed
+        assert call(alpha=1.0, a=None) == -5 and call(alpha=1.0, b=None) == -5
+        assert call(alpha=1.0, a=p + off) == -6 and call(alpha=1.0, b=p + off) == -6
+        assert call(M=0, c=None) == 0 and call(N=0, c=None) == 0
+        assert call(K=0, alpha=1.0, a=None, b=None) == 0
+
+
 def test_split_k_plan_is_a_consistent_pure_function():
     for plan, stage, nm in ((binding.gemm_f64_split_k_plan, 16, binding.gemm_f64_variant_name),
                             (binding.gemm_f32_split_k_plan, 32, binding.gemm_f32_variant_name)):
