@@ -170,6 +170,7 @@ def main():
     wall = time.perf_counter() - t0
     per_launch_ms = [events[i].elapsed_time(events[i + 1]) for i in range(args.steps)]
     kernel_ms = sum(per_launch_ms) / len(per_launch_ms)
+    kernel_ms_median = sorted(per_launch_ms)[len(per_launch_ms) // 2]
 
     ms_per_step = wall * 1e3 / args.steps
     gflops = w.flops / (ms_per_step * 1e-3) / 1e9
@@ -198,9 +199,14 @@ def main():
         "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved_tflops / peak, 4),
                      "traffic": traffic, "kernel_ms": round(kernel_ms, 4),
-                     "kernel_ms_min": round(min(per_launch_ms), 4), "kernel_ms_max": round(max(per_launch_ms), 4),
+                     "kernel_ms_min": round(min(per_launch_ms), 4), "kernel_ms_median": round(kernel_ms_median, 4),
+                     "kernel_ms_max": round(max(per_launch_ms), 4),
                      "algorithmic_flops_per_launch": w.flops, "algorithmic_bytes_per_launch": alg_bytes},
     }
+    # The peak recomputed from what the device reports (compute units x 4 SIMDs x flops per MFMA / issue cycles x clock)
+    cus, clock_khz, peak64, peak32 = binding.gemm_f64_device_peak()
+    out["roofline"]["peak_from_device_props"] = round(peak32 if f32 else peak64, 2)
+    out["config"]["clock_mhz"] = clock_khz / 1e3
     # What the matrix pipes sustain with no memory traffic at the clock the chip holds (the library's MFMA-only
     # probe), reported beside the published peak: the kernel's distance from the hardware, not from the data sheet.
     probe = binding.gemm_f32_mfma_probe if f32 else binding.gemm_f64_mfma_probe

@@ -255,6 +255,15 @@ int gemm_f64_tile_of_block(int64_t block, int64_t tiles_m, int64_t tiles_n,
  */
 int gemm_f64_mfma_probe(int64_t iterations, double *sink, int64_t sink_elems, void *stream, double *flops);
 
+/*
+ * gemm_f64_device_peak: a diagnostic.  The matrix-pipe peaks of the current device computed as the paper computes
+ * its machine peak (Section 1.2: arithmetic units x operations per cycle x clock): compute units x 4 SIMDs x 2048
+ * flop per 16x16x4 MFMA / its issue cycles (64 in double, 32 in float) x the clock rate the device reports.  Any
+ * output pointer (host) may be NULL.  256 units at 2.4 GHz give 78.6 and 157.3 TFLOP/s.  Returns
+ * GEMM_F64_ERR_LAUNCH when the device cannot be queried.  Launches nothing.
+ */
+int gemm_f64_device_peak(int *compute_units, int *clock_khz, double *fp64_mfma_tflops, double *fp32_mfma_tflops);
+
 /* Static description of a return code; never NULL, never freed. */
 const char *gemm_f64_strerror(int code);
 

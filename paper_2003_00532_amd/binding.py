@@ -83,6 +83,8 @@ def load():
     lib.gemm_f32_general.restype = ci
     lib.gemm_f32_general_ex.argtypes = [ci, ci, i64, i64, i64, cf, vp, i64, vp, i64, cf, vp, i64, vp, ci]
     lib.gemm_f32_general_ex.restype = ci
+    lib.gemm_f64_device_peak.argtypes = [ip, ip, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.gemm_f64_device_peak.restype = ci
     lib.gemm_f64_strided.argtypes = [i64, i64, i64, cd, vp, i64, i64, vp, i64, i64, cd, vp, i64, i64, vp]
     lib.gemm_f64_strided.restype = ci
     lib.gemm_f32_strided.argtypes = [i64, i64, i64, cf, vp, i64, i64, vp, i64, i64, cf, vp, i64, i64, vp]
@@ -249,6 +251,13 @@ def gemm_f64_general_ws(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C,
 def gemm_f32_general_ws(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace, workspace_bytes, stream=None):
     _check(load().gemm_f32_general_ws(int(transa), int(transb), M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
                                       _ptr(C), ldc, _ptr(workspace), int(workspace_bytes), _stream(stream)))
+
+
+def gemm_f64_device_peak():
+    """(compute units, clock in kHz, FP64 MFMA peak, FP32 MFMA peak in TFLOP/s) of the current device."""
+    cus, khz, p64, p32 = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_double(0), ctypes.c_double(0)
+    _check(load().gemm_f64_device_peak(ctypes.byref(cus), ctypes.byref(khz), ctypes.byref(p64), ctypes.byref(p32)))
+    return cus.value, khz.value, p64.value, p32.value
 
 
 def gemm_f64_strided(M, N, K, alpha, A, rsa, csa, B, rsb, csb, beta, C, rsc, csc, stream=None):

@@ -69,3 +69,21 @@ extern "C" int gemm_f32_mfma_probe(int64_t iterations, float *sink, int64_t sink
 {
     return probe<float>(iterations, sink, sink_elems, stream, flops);
 }
+
+// The machine peak computed the way the paper computes its own (Section 1.2: units per core x width x clock):
+// compute units x 4 SIMDs x flops of one 16x16x4 MFMA / its issue cycles (64 in double, 32 in float) x the
+// clock the device reports.
+extern "C" int gemm_f64_device_peak(int *compute_units, int *clock_khz, double *fp64_mfma_tflops, double *fp32_mfma_tflops)
+{
+    int dev = 0, cus = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev) != hipSuccess || cus <= 0 || khz <= 0)
+        return GEMM_F64_ERR_LAUNCH;
+    if (compute_units) *compute_units = cus;
+    if (clock_khz) *clock_khz = khz;
+    const double mfma_flops = 2.0 * 16 * 16 * 4, hz = (double)khz * 1e3;
+    if (fp64_mfma_tflops) *fp64_mfma_tflops = cus * 4 * (mfma_flops / 64.0) * hz / 1e12;
+    if (fp32_mfma_tflops) *fp32_mfma_tflops = cus * 4 * (mfma_flops / 32.0) * hz / 1e12;
+    return GEMM_F64_OK;
+}

@@ -153,6 +153,14 @@ def test_mfma_probe_runs_and_validates_its_arguments(gpu_device):
     assert load_raw().gemm_f64_mfma_probe(10, None, sink.numel(), None, None) == -5
 
 
+def test_device_peak_matches_the_published_figures_of_the_part(gpu_device):
+    cus, khz, p64, p32 = binding.gemm_f64_device_peak()
+    assert cus == torch.cuda.get_device_properties(0).multi_processor_count
+    assert p32 == 2 * p64 and abs(p64 - cus * 128 * khz * 1e3 / 1e12) < 1e-9
+    if cus == 256 and khz == 2400000:
+        assert abs(p64 - 78.6) < 0.05 and abs(p32 - 157.3) < 0.05
+
+
 def load_raw():
     return binding.load()
 

@@ -199,6 +199,19 @@ def test_strided_entry_points_validate_strides_before_any_launch():
         assert call(K=0, alpha=1.0, a=None, b=None) == 0
 
 
+def test_device_peak_query_fails_cleanly_without_a_device():
+    import ctypes as ct
+    cus, khz, p64, p32 = ct.c_int(-5), ct.c_int(-5), ct.c_double(-5), ct.c_double(-5)
+    rc = binding.load().gemm_f64_device_peak(ct.byref(cus), ct.byref(khz), ct.byref(p64), ct.byref(p32))
+    assert rc in (0, -7)
+    if rc == 0:
+        assert cus.value > 0 and khz.value > 0 and abs(p32.value - 2 * p64.value) < 1e-9
+        assert abs(p64.value - cus.value * 4 * 32 * khz.value * 1e3 / 1e12) < 1e-9
+    else:
+        assert (cus.value, khz.value, p64.value, p32.value) == (-5, -5, -5.0, -5.0)   # outputs untouched on failure
+    assert binding.load().gemm_f64_device_peak(None, None, None, None) == rc
+
+
 def test_split_k_plan_is_a_consistent_pure_function():
     for plan, stage, nm in ((binding.gemm_f64_split_k_plan, 16, binding.gemm_f64_variant_name),
                             (binding.gemm_f32_split_k_plan, 32, binding.gemm_f32_variant_name)):
