@@ -171,6 +171,20 @@ int gemm_f64_strided(int64_t M, int64_t N, int64_t K,
                      void *stream);
 
 /*
+ * gemm_f64_strided_path: the pure host-side rule behind gemm_f64_strided and gemm_f32_strided (no device is touched;
+ * the choice of kernels per layout is the tuning question of the paper's Section 2.15 Q5 applied to the layout maps
+ * of Section 2.9).  Returns 1 when a call with these sizes and strides runs on the MFMA kernels, and then writes the
+ * equivalent call of the transposed signature: *swapped = 1 means that C is column-major and the transposed problem
+ * is computed, i.e. gemm_general(*transa, *transb, N, M, K, alpha, B, *lda, A, *ldb, beta, C, *ldc); *swapped = 0
+ * means gemm_general(*transa, *transb, M, N, K, alpha, A, *lda, B, *ldb, beta, C, *ldc).  Returns 0 when the
+ * element-wise kernel is used (outputs untouched), or the negative code gemm_f64_strided would return for these
+ * sizes and strides.  Output pointers may be NULL.
+ */
+int gemm_f64_strided_path(int64_t M, int64_t N, int64_t K,
+                          int64_t rsa, int64_t csa, int64_t rsb, int64_t csb, int64_t rsc, int64_t csc,
+                          int *swapped, int *transa, int *transb, int64_t *lda, int64_t *ldb, int64_t *ldc);
+
+/*
  * gemm_f64_general_ws: gemm_f64_general with a workspace on offer (the paper's Section 2.15 Q5 asks how tuning
  * choices are to be made per problem; splitting the k range is the one choice that needs memory).  For problems of
  * few output tiles and a long k range the library may cut the range into S slices, compute the S partial products

@@ -85,6 +85,9 @@ def load():
     lib.gemm_f32_general_ex.restype = ci
     lib.gemm_f64_device_peak.argtypes = [ip, ip, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.gemm_f64_device_peak.restype = ci
+    lp = ctypes.POINTER(i64)
+    lib.gemm_f64_strided_path.argtypes = [i64] * 9 + [ip, ip, ip, lp, lp, lp]
+    lib.gemm_f64_strided_path.restype = ci
     lib.gemm_f64_strided.argtypes = [i64, i64, i64, cd, vp, i64, i64, vp, i64, i64, cd, vp, i64, i64, vp]
     lib.gemm_f64_strided.restype = ci
     lib.gemm_f32_strided.argtypes = [i64, i64, i64, cf, vp, i64, i64, vp, i64, i64, cf, vp, i64, i64, vp]
@@ -258,6 +261,20 @@ def gemm_f64_device_peak():
     cus, khz, p64, p32 = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_double(0), ctypes.c_double(0)
     _check(load().gemm_f64_device_peak(ctypes.byref(cus), ctypes.byref(khz), ctypes.byref(p64), ctypes.byref(p32)))
     return cus.value, khz.value, p64.value, p32.value
+
+
+def gemm_f64_strided_path(M, N, K, rsa, csa, rsb, csb, rsc, csc):
+    """None when the element-wise kernel would run, else (swapped, transa, transb, lda, ldb, ldc) of the equivalent
+    call of the transposed signature; raises for sizes or strides that gemm_f64_strided rejects."""
+    sw, ta, tb = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+    lda, ldb, ldc = ctypes.c_int64(0), ctypes.c_int64(0), ctypes.c_int64(0)
+    rc = load().gemm_f64_strided_path(M, N, K, rsa, csa, rsb, csb, rsc, csc, ctypes.byref(sw), ctypes.byref(ta), ctypes.byref(tb),
+                                      ctypes.byref(lda), ctypes.byref(ldb), ctypes.byref(ldc))
+    if rc < 0:
+        _check(rc)
+    if rc == 0:
+        return None
+    return bool(sw.value), ta.value, tb.value, lda.value, ldb.value, ldc.value
 
 
 def gemm_f64_strided(M, N, K, alpha, A, rsa, csa, B, rsb, csb, beta, C, rsc, csc, stream=None):

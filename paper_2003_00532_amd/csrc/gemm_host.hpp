@@ -331,9 +331,17 @@ inline Layout classify(int64_t rows, int64_t cols, int64_t rs, int64_t cs, int64
 // C^T = B^T A^T, which sums the same products in the same order) and runs on the tiled kernels; otherwise the
 // element-wise kernel computes it.  The elements of C must be distinct: one of its strides must span the whole
 // extent of the other.
-template <typename T>
-int gemm_strided(const Variant *variants, int count, int64_t M, int64_t N, int64_t K, T alpha, const T *A, int64_t rsa,
-                 int64_t csa, const T *B, int64_t rsb, int64_t csb, T beta, T *C, int64_t rsc, int64_t csc, void *stream_)
+// What a strided call becomes: the transposed-signature call on the tiled kernels (tiled == true; operands swapped
+// when C is column-major) or the element-wise kernel.
+struct StridedPath {
+    bool tiled, swapped;
+    int transa, transb;         // of the call as issued, i.e. after the swap
+    int64_t lda, ldb, ldc;      // likewise
+};
+
+// Validation of the strides alone (what needs no pointers), shared by the entry point and the host-side query.
+inline int validate_strides(int64_t M, int64_t N, int64_t K, int64_t rsa, int64_t csa, int64_t rsb, int64_t csb, int64_t rsc,
+                            int64_t csc)
 {
     if (M < 0 || N < 0 || K < 0) return GEMM_F64_ERR_DIM;
     if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
@@ -344,6 +352,27 @@ int gemm_strided(const Variant *variants, int count, int64_t M, int64_t N, int64
         const __int128 row_span = (__int128)csc * (N - 1) + 1, col_span = (__int128)rsc * (M - 1) + 1;
         if (!((__int128)rsc >= row_span || (__int128)csc >= col_span)) return GEMM_F64_ERR_LDC;
     }
+    return GEMM_F64_OK;
+}
+
+inline StridedPath strided_path(int64_t M, int64_t N, int64_t K, int64_t rsa, int64_t csa, int64_t rsb, int64_t csb,
+                                int64_t rsc, int64_t csc)
+{
+    int64_t lda = 1, ldb = 1, ldc = 1;
+    const Layout la = classify(M, K, rsa, csa, &lda), lb = classify(K, N, rsb, csb, &ldb), lc = classify(M, N, rsc, csc, &ldc);
+    if (la == kNeither || lb == kNeither || lc == kNeither) return StridedPath{false, false, 0, 0, 0, 0, 0};
+    const int ta = la == kColumns, tb = lb == kColumns;
+    if (lc == kRows) return StridedPath{true, false, ta, tb, lda, ldb, ldc};
+    // C^T (N x M, row-major with leading dimension csc) = alpha * B^T A^T + beta * C^T
+    return StridedPath{true, true, !tb, !ta, ldb, lda, ldc};
+}
+
+template <typename T>
+int gemm_strided(const Variant *variants, int count, int64_t M, int64_t N, int64_t K, T alpha, const T *A, int64_t rsa,
+                 int64_t csa, const T *B, int64_t rsb, int64_t csb, T beta, T *C, int64_t rsc, int64_t csc, void *stream_)
+{
+    const int rc = validate_strides(M, N, K, rsa, csa, rsb, csb, rsc, csc);
+    if (rc != GEMM_F64_OK) return rc;
     const bool product = (alpha != T(0)) && K != 0;
     const bool c_live = M > 0 && N > 0, ab_live = c_live && product;
     if (c_live && C == nullptr) return GEMM_F64_ERR_NULL;
@@ -354,13 +383,13 @@ int gemm_strided(const Variant *variants, int count, int64_t M, int64_t N, int64
     if (!c_live) return GEMM_F64_OK;
     if (ceil_div(M * N, 256) > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
 
-    int64_t lda = 1, ldb = 1, ldc = 1;
-    const Layout la = classify(M, K, rsa, csa, &lda), lb = classify(K, N, rsb, csb, &ldb), lc = classify(M, N, rsc, csc, &ldc);
-    if (la != kNeither && lb != kNeither && lc != kNeither) {
-        const int ta = la == kColumns, tb = lb == kColumns;
-        if (lc == kRows) return gemm_ex<T>(variants, count, ta, tb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream_, -1);
-        // C^T (N x M, row-major with leading dimension csc) = alpha * B^T A^T + beta * C^T
-        return gemm_ex<T>(variants, count, !tb, !ta, N, M, K, alpha, B, ldb, A, lda, beta, C, ldc, stream_, -1);
+    const StridedPath path = strided_path(M, N, K, rsa, csa, rsb, csb, rsc, csc);
+    if (path.tiled) {
+        if (!path.swapped)
+            return gemm_ex<T>(variants, count, path.transa, path.transb, M, N, K, alpha, A, path.lda, B, path.ldb, beta, C,
+                              path.ldc, stream_, -1);
+        return gemm_ex<T>(variants, count, path.transa, path.transb, N, M, K, alpha, B, path.lda, A, path.ldb, beta, C, path.ldc,
+                          stream_, -1);
     }
     hipStream_t stream = (hipStream_t)stream_;
     const int m = (int)M, n = (int)N, k = (int)K;

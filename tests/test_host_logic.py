@@ -199,6 +199,61 @@ def test_strided_entry_points_validate_strides_before_any_launch():
         assert call(K=0, alpha=1.0, a=None, b=None) == 0
 
 
+def test_strided_path_addresses_the_same_elements_as_the_strides():
+    # whenever the rule maps a strided call onto the transposed signature, every element of every operand must sit at
+    # the address the strides give; whenever it does not, some operand really has no unit-stride description
+    import itertools
+    import numpy as np
+    rng = np.random.default_rng(0)
+    tiled = elementwise = 0
+    for M, N, K in itertools.product([1, 2, 3, 5], repeat=3):
+        for _ in range(40):
+            def pick(rows, cols):
+                kind = rng.integers(5)
+                if kind == 0: return (cols + int(rng.integers(3)), 1)          # row-major, maybe padded
+                if kind == 1: return (1, rows + int(rng.integers(3)))          # column-major, maybe padded
+                if kind == 2: return (2 * cols + 1, 2)                         # sampled
+                if kind == 3: return (1, 1)                                    # overlapping unless a vector
+                return (int(rng.integers(1, 9)), int(rng.integers(1, 9)))
+            (rsa, csa), (rsb, csb), (rsc, csc) = pick(M, K), pick(K, N), pick(M, N)
+            try:
+                path = binding.gemm_f64_strided_path(M, N, K, rsa, csa, rsb, csb, rsc, csc)
+            except binding.GemmF64Error as e:
+                assert e.code == -4    # only C can be rejected here: its elements would overlap
+                span_r, span_c = csc * (N - 1) + 1, rsc * (M - 1) + 1
+                assert M > 1 and N > 1 and rsc < span_r and csc < span_c
+                continue
+            i, j, k = np.arange(M)[:, None], np.arange(N)[None, :], np.arange(K)
+            a_addr = np.arange(M)[:, None] * rsa + k[None, :] * csa
+            b_addr = k[:, None] * rsb + np.arange(N)[None, :] * csb
+            c_addr = i * rsc + j * csc
+            assert len(set(c_addr.ravel().tolist())) == M * N, "accepted a C whose elements overlap"
+            if path is None:
+                elementwise += 1
+                def unit(rows, cols, rs, cs):
+                    return ((cs == 1 or cols == 1) and (rs >= cols or rows == 1)) or ((rs == 1 or rows == 1) and (cs >= rows or cols == 1))
+                assert not (unit(M, K, rsa, csa) and unit(K, N, rsb, csb) and unit(M, N, rsc, csc))
+                continue
+            tiled += 1
+            swapped, ta, tb, lda, ldb, ldc = path
+            def op(t, rows, cols, ld):     # addresses of a rows x cols operand of the transposed signature
+                r, c = np.arange(rows)[:, None], np.arange(cols)[None, :]
+                assert ld >= max(1, rows if t else cols)
+                return c * ld + r if t else r * ld + c
+            if not swapped:
+                assert np.array_equal(op(ta, M, K, lda), a_addr) and np.array_equal(op(tb, K, N, ldb), b_addr)
+                assert np.array_equal(op(0, M, N, ldc), c_addr)
+            else:
+                assert np.array_equal(op(ta, N, K, lda), b_addr.T) and np.array_equal(op(tb, K, M, ldb), a_addr.T)
+                assert np.array_equal(op(0, N, M, ldc), c_addr.T)
+    assert tiled > 200 and elementwise > 200
+    # the conventional cases by name
+    assert binding.gemm_f64_strided_path(100, 80, 60, 60, 1, 80, 1, 80, 1) == (False, 0, 0, 60, 80, 80)      # all row-major
+    assert binding.gemm_f64_strided_path(100, 80, 60, 1, 100, 1, 60, 1, 100) == (True, 0, 0, 60, 100, 100)   # all column-major
+    assert binding.gemm_f64_strided_path(100, 80, 60, 1, 100, 80, 1, 80, 1) == (False, 1, 0, 100, 80, 80)    # A^T B
+    assert binding.gemm_f64_strided_path(100, 80, 60, 128, 2, 80, 1, 80, 1) is None                          # sampled A
+
+
 def test_device_peak_query_fails_cleanly_without_a_device():
     import ctypes as ct
     cus, khz, p64, p32 = ct.c_int(-5), ct.c_int(-5), ct.c_double(-5), ct.c_double(-5)
