@@ -176,6 +176,10 @@ struct Job {
     hipStream_t stream;
     int slices;     // grid height
     SplitK split;
+    // Sampled operands: elements es.a / es.b apart along the contiguous index, or leading dimensions that do not
+    // cover a row; such a job runs in the kSampled mode (64 x 64 tile only) whatever its other properties.
+    bool sampled = false;
+    ElemStrides es{1, 1};
 };
 
 template <typename T, int BM, int BN, int WM, int WN, bool TA, bool TB>
@@ -184,18 +188,28 @@ hipError_t launch_mfma_t(const Job<T> &j)
     constexpr int BK = 8 * (16 / (int)sizeof(T));
     const int tiles_m = (int)ceil_div(j.M, BM), tiles_n = (int)ceil_div(j.N, BN);
     const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n), (unsigned)j.slices), block(kThreads);
+    if (j.sampled) {
+        // built for one tile shape only (the mode needs more registers than the largest tile leaves)
+        if constexpr (BM == 64 && BN == 64) {
+            hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kSampled, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
+                               j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, tiles_m, tiles_n, j.split, j.es);
+            return hipGetLastError();
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
     const bool vec = async_copies_possible<T>(j.lda, j.ldb);
     // The lean kernel assumes full tiles everywhere and whole K stages (in every slice).
     const bool lean = vec && (j.M % BM == 0) && (j.N % BN == 0) && (j.K % BK == 0) && (j.split.k_chunk % BK == 0);
     if (lean)
         hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kLean, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
-                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, tiles_m, tiles_n, j.split);
+                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, tiles_m, tiles_n, j.split, j.es);
     else if (vec)
         hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kGeneric, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
-                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, tiles_m, tiles_n, j.split);
+                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, tiles_m, tiles_n, j.split, j.es);
     else
         hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kStaged, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
-                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, tiles_m, tiles_n, j.split);
+                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, tiles_m, tiles_n, j.split, j.es);
     return hipGetLastError();
 }
 
@@ -331,12 +345,17 @@ inline Layout classify(int64_t rows, int64_t cols, int64_t rs, int64_t cs, int64
 // C^T = B^T A^T, which sums the same products in the same order) and runs on the tiled kernels; otherwise the
 // element-wise kernel computes it.  The elements of C must be distinct: one of its strides must span the whole
 // extent of the other.
-// What a strided call becomes: the transposed-signature call on the tiled kernels (tiled == true; operands swapped
-// when C is column-major) or the element-wise kernel.
+// What a strided call becomes.  kTransposed: the transposed-signature call on the tiled kernels.  kSampled: the tiled
+// kernels in their register-staged mode, because op(A) or op(B) has no unit stride or no leading dimension that
+// covers its rows (es_a / es_b are the element strides along the index the kernel treats as contiguous).
+// kElementwise: C itself has no unit stride.  For the first two, a column-major C means that the transposed
+// problem C^T = B^T A^T is what runs (swapped), and every field describes that call as issued.
 struct StridedPath {
-    bool tiled, swapped;
-    int transa, transb;         // of the call as issued, i.e. after the swap
-    int64_t lda, ldb, ldc;      // likewise
+    enum Kind { kElementwise = 0, kTransposed = 1, kSampled = 2 } kind;
+    bool swapped;
+    int transa, transb;
+    int64_t lda, ldb, ldc;
+    int64_t es_a, es_b;
 };
 
 // Validation of the strides alone (what needs no pointers), shared by the entry point and the host-side query.
@@ -358,13 +377,34 @@ inline int validate_strides(int64_t M, int64_t N, int64_t K, int64_t rsa, int64_
 inline StridedPath strided_path(int64_t M, int64_t N, int64_t K, int64_t rsa, int64_t csa, int64_t rsb, int64_t csb,
                                 int64_t rsc, int64_t csc)
 {
-    int64_t lda = 1, ldb = 1, ldc = 1;
-    const Layout la = classify(M, K, rsa, csa, &lda), lb = classify(K, N, rsb, csb, &ldb), lc = classify(M, N, rsc, csc, &ldc);
-    if (la == kNeither || lb == kNeither || lc == kNeither) return StridedPath{false, false, 0, 0, 0, 0, 0};
-    const int ta = la == kColumns, tb = lb == kColumns;
-    if (lc == kRows) return StridedPath{true, false, ta, tb, lda, ldb, ldc};
-    // C^T (N x M, row-major with leading dimension csc) = alpha * B^T A^T + beta * C^T
-    return StridedPath{true, true, !tb, !ta, ldb, lda, ldc};
+    StridedPath p{StridedPath::kElementwise, false, 0, 0, 1, 1, 1, 1, 1};
+    const Layout lc = classify(M, N, rsc, csc, &p.ldc);
+    if (lc == kNeither) return p;
+    p.swapped = lc == kColumns;
+    // first operand F (rows x K) and second operand S (K x cols) of the row-major problem: A and B, or, for a
+    // column-major C, B^T and A^T (C^T = B^T A^T; transposing an operand swaps its two strides)
+    const int64_t rows = p.swapped ? N : M, cols = p.swapped ? M : N;
+    const int64_t rsf = p.swapped ? csb : rsa, csf = p.swapped ? rsb : csa;
+    const int64_t rss = p.swapped ? csa : rsb, css = p.swapped ? rsa : csb;
+    const Layout lf = classify(rows, K, rsf, csf, &p.lda), ls = classify(K, cols, rss, css, &p.ldb);
+    p.transa = lf == kColumns;
+    p.transb = ls == kColumns;
+    if (lf != kNeither && ls != kNeither) {
+        p.kind = StridedPath::kTransposed;
+        return p;
+    }
+    p.kind = StridedPath::kSampled;
+    if (lf == kNeither) {   // F(x, k) = F[x * rsf + k * csf]: treat the direction of the smaller stride as contiguous
+        p.transa = csf > rsf;
+        p.lda = p.transa ? csf : rsf;
+        p.es_a = p.transa ? rsf : csf;
+    }
+    if (ls == kNeither) {   // S(k, x) = S[k * rss + x * css]
+        p.transb = rss <= css;
+        p.ldb = p.transb ? css : rss;
+        p.es_b = p.transb ? rss : css;
+    }
+    return p;
 }
 
 template <typename T>
@@ -384,18 +424,23 @@ int gemm_strided(const Variant *variants, int count, int64_t M, int64_t N, int64
     if (ceil_div(M * N, 256) > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
 
     const StridedPath path = strided_path(M, N, K, rsa, csa, rsb, csb, rsc, csc);
-    if (path.tiled) {
-        if (!path.swapped)
-            return gemm_ex<T>(variants, count, path.transa, path.transb, M, N, K, alpha, A, path.lda, B, path.ldb, beta, C,
-                              path.ldc, stream_, -1);
-        return gemm_ex<T>(variants, count, path.transa, path.transb, N, M, K, alpha, B, path.lda, A, path.ldb, beta, C, path.ldc,
-                          stream_, -1);
-    }
+    const T *F = path.swapped ? B : A, *S = path.swapped ? A : B;
+    const int64_t rows = path.swapped ? N : M, cols = path.swapped ? M : N;
+    if (path.kind == StridedPath::kTransposed)
+        return gemm_ex<T>(variants, count, path.transa, path.transb, rows, cols, K, alpha, F, path.lda, S, path.ldb, beta, C,
+                          path.ldc, stream_, -1);
     hipStream_t stream = (hipStream_t)stream_;
     const int m = (int)M, n = (int)N, k = (int)K;
     if (!product) {
         if (beta == T(1)) return GEMM_F64_OK;
         return launch_scale<T>(m, n, beta, C, rsc, csc, stream) == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
+    }
+    if (path.kind == StridedPath::kSampled) {
+        Job<T> job{path.transa, path.transb, (int)rows, (int)cols, k, alpha, F, path.lda, S, path.ldb, beta, C, path.ldc, stream,
+                   1, SplitK{k, 0, 0, 0}};
+        job.sampled = true;
+        job.es = ElemStrides{path.es_a, path.es_b};
+        return launch_mfma<T, 64, 64, 2, 2>(job) == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
     }
     const dim3 grid((unsigned)ceil_div(M * N, 256)), block(256);
     hipLaunchKernelGGL(gemm_naive_kernel<T>, grid, block, 0, stream, m, n, k, alpha, A, rsa, csa, B, rsb, csb, beta, C, rsc, csc);

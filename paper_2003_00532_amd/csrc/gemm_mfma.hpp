@@ -38,7 +38,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 constexpr int kXcds = 8;    // workgroups are dealt round-robin to 8 XCDs, each with a private L2
 constexpr int kGroupM = 8;  // tile rows per group of the grouped tile order
 constexpr int kThreads = 256;
-constexpr int kLean = 0, kGeneric = 1, kStaged = 2;  // kernel modes, see gemm_mfma_kernel
+constexpr int kLean = 0, kGeneric = 1, kStaged = 2, kSampled = 3;  // kernel modes, see gemm_mfma_kernel
 
 // What depends on the element type.  A 16-byte LDS cell holds E consecutive k (for A) of one row;
 // one LDS stage is 8 cells deep, so BK = 8 * E (16 for double, 32 for float).
@@ -70,6 +70,12 @@ template <> struct Elem<float> {
 struct SplitK {
     int k_chunk;
     int64_t step_a, step_b, step_c;
+};
+
+// Elements between neighbours along the contiguous index of op(A) and op(B); read by the kSampled mode only
+// (1 everywhere else).
+struct ElemStrides {
+    int64_t a, b;
 };
 
 // Workgroup id -> tile coordinates.  Block b runs on XCD b % kXcds.  Each XCD receives a
@@ -174,9 +180,12 @@ __device__ __forceinline__ T scaled_update(T alpha, T s, T beta, T c, bool read_
 // LDS cells keep stale bits, which again only feed outputs never stored) and a partly valid last cell
 // is fetched on its own, four bytes per lane.
 //
-// The VGPR path (load_regs / store_regs: ragged last K stage, very large leading dimensions) loads element-wise,
-// with zeros outside the logical matrix, and writes the same LDS layout.  Both operands are zeroed for
-// k >= K, so padding only ever forms 0 * 0.
+// The VGPR path (load_regs / store_regs: ragged last K stage, very large leading dimensions, operands sampled
+// with a stride in both directions) loads element-wise, with zeros outside the logical matrix, and writes the
+// same LDS layout.  Both operands are zeroed for k >= K, so padding only ever forms 0 * 0.  Only this path
+// knows an element stride `es` along the contiguous index: element (x, k) sits at P[x * ld + k * es]
+// (KMAJOR) or P[k * ld + x * es]; the asynchronous copies need es == 1, and every mode but kSampled passes
+// the literal 1.
 template <typename T, bool KMAJOR, int BX, bool GENERIC>
 struct Panel {
     typedef Elem<T> EL;
@@ -213,15 +222,16 @@ struct Panel {
 
     const T *P;
     int64_t ld;
+    int64_t es;   // elements between neighbours along the panel's contiguous index; other than 1 on the VGPR path only
     int x0, X, K;
     int w, l, lg, li;
     uint32_t voff[KMAJOR ? CHUNKS_PER_WAVE : 1];
     const char *base;
     bool edge;
 
-    __device__ __forceinline__ void init(const T *P_, int64_t ld_, int x0_, int X_, int K_, int w_, int l_)
+    __device__ __forceinline__ void init(const T *P_, int64_t ld_, int64_t es_, int x0_, int X_, int K_, int w_, int l_)
     {
-        P = P_; ld = ld_; x0 = x0_; X = X_; K = K_; w = w_; l = l_;
+        P = P_; ld = ld_; es = es_; x0 = x0_; X = X_; K = K_; w = w_; l = l_;
         lg = l >> 4; li = l & 15;
         edge = GENERIC && (x0 + BX > X);
         if constexpr (KMAJOR) {
@@ -287,14 +297,14 @@ struct Panel {
         for (int q = 0; q < NR; ++q) {
             if constexpr (KMAJOR) {
                 const int row = x0 + vg_row(q), k = k0 + E * vg_cell(q);
-                const T *p = P + (int64_t)row * ld + k;
+                const T *p = P + (int64_t)row * ld + k * es;
 #pragma unroll
-                for (int e = 0; e < E; ++e) r[E * q + e] = (row < X && k + e < K) ? p[e] : T(0);
+                for (int e = 0; e < E; ++e) r[E * q + e] = (row < X && k + e < K) ? p[e * es] : T(0);
             } else {
                 const int kk = k0 + l / CPR + (64 / CPR) * w + (kThreads / CPR) * q, col = x0 + E * (l % CPR);
-                const T *p = P + (int64_t)kk * ld + col;
+                const T *p = P + (int64_t)kk * ld + col * es;
 #pragma unroll
-                for (int e = 0; e < E; ++e) r[E * q + e] = (kk < K && col + e < X) ? p[e] : T(0);
+                for (int e = 0; e < E; ++e) r[E * q + e] = (kk < K && col + e < X) ? p[e * es] : T(0);
             }
         }
     }
@@ -355,12 +365,15 @@ struct Panel {
 // ahead, at the price of 16 to 32 more live registers and of vector-ALU work in the K loop.  It
 // addresses memory with 64-bit pointers and is what remains for leading dimensions too large for the
 // 32-bit lane offsets of the asynchronous copies.
+// MODE = kSampled is kStaged for operands whose elements are `es` apart along their contiguous index (a matrix
+// sampled with a stride in both directions); it is the only mode that reads `es`, and costs a few more
+// registers, so it is built for the 64 x 64 tile only.
 // (Asking the compiler for more than two waves per SIMD was measured to cost 3 to 25 % on the larger
 // tiles: it then schedules the K loop differently; the smaller tiles fit more waves anyway.)
 template <typename T, int BM, int BN, int WM, int WN, int MODE, bool TA, bool TB>
 __global__ void __launch_bounds__(kThreads, 2)
 gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, int64_t lda, const T *__restrict__ B_,
-                 int64_t ldb, T beta, T *__restrict__ C_, int64_t ldc, int tiles_m, int tiles_n, SplitK split)
+                 int64_t ldb, T beta, T *__restrict__ C_, int64_t ldc, int tiles_m, int tiles_n, SplitK split, ElemStrides es)
 {
     // this workgroup's slice of k (all of it when the grid has height 1)
     const int slice = blockIdx.y;
@@ -376,8 +389,9 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, i
     static_assert(E * SZ == 16, "a cell is 16 bytes");
     constexpr int BK = 8 * E;
     constexpr bool GENERIC = MODE != kLean;
-    constexpr bool STAGED = MODE == kStaged;
-    static_assert(MODE == kLean || MODE == kGeneric || MODE == kStaged, "kernel mode");
+    constexpr bool STAGED = MODE == kStaged || MODE == kSampled;
+    constexpr bool SAMPLED = MODE == kSampled;
+    static_assert(MODE == kLean || MODE == kGeneric || MODE == kStaged || MODE == kSampled, "kernel mode");
     static_assert(WM * WN == 4, "four waves per workgroup");
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int MI = TM / 16, NI = TN / 16;
@@ -408,8 +422,8 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, i
 
     PA pa;
     PB pb;
-    pa.init(A, lda, m0, M, K, w, l);
-    pb.init(B, ldb, n0, N, K, w, l);
+    pa.init(A, lda, SAMPLED ? es.a : 1, m0, M, K, w, l);
+    pb.init(B, ldb, SAMPLED ? es.b : 1, n0, N, K, w, l);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
 
     auto fetch_sync = [&](int kt, int buf) {

@@ -135,15 +135,40 @@ def test_unit_stride_layouts_over_several_tiles(gpu_device, kind, dtype):
 
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 @pytest.mark.parametrize("kind", ["int", "uniform"])
-def test_sampled_layouts_take_the_element_wise_path(gpu_device, kind, dtype):
+def test_sampled_layouts(gpu_device, kind, dtype):
+    # sampled A or B with a unit-stride C run on the tiled kernels (gathered into the staging buffers), a sampled C
+    # on the element-wise kernel
     t = 0
-    for (M, N, K) in [(70, 50, 90), (33, 129, 64), (150, 7, 40)]:
+    for (M, N, K) in [(70, 50, 90), (33, 129, 64), (150, 7, 40), (200, 264, 150)]:
         A, B, C0 = _operands(200 + t, M, N, K, kind, dtype)
         for trip in [("row_step2", "row", "row"), ("row", "col_step3", "col"), ("col", "row", "row_step2"),
-                     ("col_step3", "row_step2", "col_step3"), ("row", "row", "col_step3")]:
+                     ("col_step3", "row_step2", "col_step3"), ("row", "row", "col_step3"), ("col_step3", "row_step2", "row"),
+                     ("row_step2", "col_step3", "col"), ("col", "row_step2", "col")]:
             alpha, beta = [(1.0, 1.0), (-1.5, 0.5), (2.0, 0.0)][t % 3]
             t += 1
             _check(alpha, A, B, beta, C0, trip, kind, "%s %s %s" % ((M, N, K), trip, kind))
+
+
+def test_the_path_rule_agrees_with_what_the_tests_above_assume():
+    assert binding.gemm_f64_strided_path(70, 50, 90, 2 * 90 + 5, 2, 52, 1, 52, 1)[0] == 2       # row_step2, row, row
+    assert binding.gemm_f64_strided_path(70, 50, 90, 92, 1, 52, 1, 2 * 50 + 5, 2) is None       # row, row, row_step2
+    assert binding.gemm_f64_strided_path(70, 50, 90, 92, 1, 1, 93, 1, 73)[0] == 1               # row, col, col
+
+
+def test_overlapping_read_only_operands_run_on_the_tiled_kernels(gpu_device):
+    # A(i, k) = v[i + k] (strides 1, 1) and B(k, j) = w[2 k + j] (strides 2, 1) over several tiles
+    M, N, K = 150, 140, 170
+    rng = np.random.default_rng(9)
+    v = rng.integers(-4, 5, size=M + K).astype(np.float64)
+    w = rng.integers(-4, 5, size=2 * K + N).astype(np.float64)
+    Av = np.lib.stride_tricks.as_strided(v, shape=(M, K), strides=(8, 8))
+    Bv = np.lib.stride_tricks.as_strided(w, shape=(K, N), strides=(16, 8))
+    assert binding.gemm_f64_strided_path(M, N, K, 1, 1, 2, 1, N, 1)[0] == 2
+    C = np.zeros((M, N))
+    device_call(1.0, Av, Bv, 0.0, C)
+    want = np.zeros((M, N))
+    oracle.gemm_strided_ref(1.0, Av, Bv, 0.0, want)
+    pins.assert_bitwise(C, want, "Hankel operands")
 
 
 def test_column_major_call_is_the_transposed_problem_bit_for_bit(gpu_device):

@@ -200,14 +200,19 @@ def test_strided_entry_points_validate_strides_before_any_launch():
 
 
 def test_strided_path_addresses_the_same_elements_as_the_strides():
-    # whenever the rule maps a strided call onto the transposed signature, every element of every operand must sit at
-    # the address the strides give; whenever it does not, some operand really has no unit-stride description
+    # whenever the rule maps a strided call onto the tiled kernels, every element of every operand must sit at the
+    # address the strides give; the transposed signature is claimed exactly when all three operands have a
+    # unit-stride description, the element-wise kernel exactly when C has none
     import itertools
     import numpy as np
     rng = np.random.default_rng(0)
-    tiled = elementwise = 0
+    counts = {0: 0, 1: 0, 2: 0}
+
+    def unit(rows, cols, rs, cs):
+        return ((cs == 1 or cols == 1) and (rs >= cols or rows == 1)) or ((rs == 1 or rows == 1) and (cs >= rows or cols == 1))
+
     for M, N, K in itertools.product([1, 2, 3, 5], repeat=3):
-        for _ in range(40):
+        for _ in range(60):
             def pick(rows, cols):
                 kind = rng.integers(5)
                 if kind == 0: return (cols + int(rng.integers(3)), 1)          # row-major, maybe padded
@@ -224,34 +229,40 @@ def test_strided_path_addresses_the_same_elements_as_the_strides():
                 assert M > 1 and N > 1 and rsc < span_r and csc < span_c
                 continue
             i, j, k = np.arange(M)[:, None], np.arange(N)[None, :], np.arange(K)
-            a_addr = np.arange(M)[:, None] * rsa + k[None, :] * csa
-            b_addr = k[:, None] * rsb + np.arange(N)[None, :] * csb
+            a_addr = i * rsa + k[None, :] * csa
+            b_addr = k[:, None] * rsb + j * csb
             c_addr = i * rsc + j * csc
             assert len(set(c_addr.ravel().tolist())) == M * N, "accepted a C whose elements overlap"
             if path is None:
-                elementwise += 1
-                def unit(rows, cols, rs, cs):
-                    return ((cs == 1 or cols == 1) and (rs >= cols or rows == 1)) or ((rs == 1 or rows == 1) and (cs >= rows or cols == 1))
-                assert not (unit(M, K, rsa, csa) and unit(K, N, rsb, csb) and unit(M, N, rsc, csc))
+                counts[0] += 1
+                assert not unit(M, N, rsc, csc)
                 continue
-            tiled += 1
-            swapped, ta, tb, lda, ldb, ldc = path
-            def op(t, rows, cols, ld):     # addresses of a rows x cols operand of the transposed signature
-                r, c = np.arange(rows)[:, None], np.arange(cols)[None, :]
-                assert ld >= max(1, rows if t else cols)
-                return c * ld + r if t else r * ld + c
+            kind, swapped, ta, tb, lda, ldb, ldc, es_a, es_b = path
+            counts[kind] += 1
+            assert unit(M, N, rsc, csc)
+            all_unit = unit(M, K, rsa, csa) and unit(K, N, rsb, csb)
+            assert (kind == 1) == all_unit
+            if kind == 1:
+                assert es_a == 1 and es_b == 1
+            rows, cols = (N, M) if swapped else (M, N)
+            x_f, x_s, kk = np.arange(rows)[:, None], np.arange(cols)[None, :], np.arange(K)
+            f_addr = kk[None, :] * lda + x_f * es_a if ta else x_f * lda + kk[None, :] * es_a      # F(x, k), rows x K
+            s_addr = x_s * ldb + kk[:, None] * es_b if tb else kk[:, None] * ldb + x_s * es_b      # S(k, x), K x cols
+            o_addr = np.arange(rows)[:, None] * ldc + np.arange(cols)[None, :]
+            if kind == 1:   # a legal call of the transposed signature
+                assert lda >= max(1, rows if ta else K) and ldb >= max(1, K if tb else cols)
+            assert ldc >= max(1, cols)
             if not swapped:
-                assert np.array_equal(op(ta, M, K, lda), a_addr) and np.array_equal(op(tb, K, N, ldb), b_addr)
-                assert np.array_equal(op(0, M, N, ldc), c_addr)
+                assert np.array_equal(f_addr, a_addr) and np.array_equal(s_addr, b_addr) and np.array_equal(o_addr, c_addr)
             else:
-                assert np.array_equal(op(ta, N, K, lda), b_addr.T) and np.array_equal(op(tb, K, M, ldb), a_addr.T)
-                assert np.array_equal(op(0, N, M, ldc), c_addr.T)
-    assert tiled > 200 and elementwise > 200
+                assert np.array_equal(f_addr, b_addr.T) and np.array_equal(s_addr, a_addr.T) and np.array_equal(o_addr, c_addr.T)
+    assert min(counts.values()) > 200, counts
     # the conventional cases by name
-    assert binding.gemm_f64_strided_path(100, 80, 60, 60, 1, 80, 1, 80, 1) == (False, 0, 0, 60, 80, 80)      # all row-major
-    assert binding.gemm_f64_strided_path(100, 80, 60, 1, 100, 1, 60, 1, 100) == (True, 0, 0, 60, 100, 100)   # all column-major
-    assert binding.gemm_f64_strided_path(100, 80, 60, 1, 100, 80, 1, 80, 1) == (False, 1, 0, 100, 80, 80)    # A^T B
-    assert binding.gemm_f64_strided_path(100, 80, 60, 128, 2, 80, 1, 80, 1) is None                          # sampled A
+    assert binding.gemm_f64_strided_path(100, 80, 60, 60, 1, 80, 1, 80, 1) == (1, False, 0, 0, 60, 80, 80, 1, 1)      # all row-major
+    assert binding.gemm_f64_strided_path(100, 80, 60, 1, 100, 1, 60, 1, 100) == (1, True, 0, 0, 60, 100, 100, 1, 1)   # all column-major
+    assert binding.gemm_f64_strided_path(100, 80, 60, 1, 100, 80, 1, 80, 1) == (1, False, 1, 0, 100, 80, 80, 1, 1)    # A^T B
+    assert binding.gemm_f64_strided_path(100, 80, 60, 128, 2, 80, 1, 80, 1) == (2, False, 0, 0, 128, 80, 80, 2, 1)    # sampled A
+    assert binding.gemm_f64_strided_path(100, 80, 60, 60, 1, 80, 1, 2 * 80, 2) is None                                 # sampled C
 
 
 def test_device_peak_query_fails_cleanly_without_a_device():
