@@ -30,10 +30,10 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), scaled
 # by the copy-kernel calibration; None until measured for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/dgemm_mfma_128x128x16_c3_8192_pmc.txt: FETCH_SIZE 6 669 100 KiB x 2.0 + WRITE_SIZE 524 288 KiB x 1.0
-    ("c3_8192", "mfma_128x128x16"): (6669100 * 2.0 + 524288 * 1.0) * 1024,
-    # profiles/sgemm_mfma_128x128x32_c3_8192_pmc.txt: FETCH_SIZE 3 322 970 KiB x 2.0 + WRITE_SIZE 262 226 KiB x 1.0
-    ("c3_8192", "mfma_128x128x32"): (3322970 * 2.0 + 262226 * 1.0) * 1024,
+    # profiles/dgemm_mfma_128x128x16_c3_8192_pmc.txt: FETCH_SIZE 6 633 980 KiB x 2.0 + WRITE_SIZE 524 288 KiB x 1.0
+    ("c3_8192", "mfma_128x128x16"): (6633980 * 2.0 + 524288 * 1.0) * 1024,
+    # profiles/sgemm_mfma_128x128x32_c3_8192_pmc.txt: FETCH_SIZE 3 307 360 KiB x 2.0 + WRITE_SIZE 262 228 KiB x 1.0
+    ("c3_8192", "mfma_128x128x32"): (3307360 * 2.0 + 262228 * 1.0) * 1024,
 }
 
 
