@@ -208,3 +208,53 @@ def test_large_column_major_problem_matches_the_exact_integer_product(gpu_device
     want = np.ascontiguousarray(C0[rows].cpu().numpy())
     oracle.gemm_strided_ref(-2.0, np.ascontiguousarray(A[rows].cpu().numpy()), B.cpu().numpy(), 1.0, want)
     pins.assert_bitwise(dC[:, :M].t()[rows].cpu().numpy(), want, "oracle rows")
+
+
+def test_seeded_random_layouts_match_the_exact_integer_product(gpu_device):
+    # random shapes around the tile edges, random layouts per operand (padded, sampled, overlapping for A and B),
+    # small integers: every correct evaluation is exact, so the product computed by the vendor library on gathered
+    # copies is the answer (secondary to the oracle-based tests above); nothing outside C's elements may change
+    rng = np.random.default_rng(2024)
+    edges = [1, 2, 15, 16, 17, 31, 33, 63, 64, 65, 127, 129, 191, 193, 257]
+    dim = lambda hi: int(rng.choice(edges)) if rng.random() < 0.5 else int(rng.integers(1, hi + 1))
+
+    def layout(rows, cols, sampled_ok=True):
+        kind, pad, s = int(rng.integers(6 if sampled_ok else 2)), int(rng.integers(0, 4)), int(rng.integers(2, 4))
+        return [(cols + pad, 1), (1, rows + pad), (s * cols + pad, s), (s, s * rows + pad),
+                (int(rng.integers(1, 4)), int(rng.integers(1, 4))), (s * (cols + pad), 1)][kind]
+
+    span = lambda r, c, rs, cs: (max(r, 1) - 1) * rs + (max(c, 1) - 1) * cs + 1
+    seen = {None: 0, 1: 0, 2: 0}
+    for case in range(400):
+        f32 = bool(rng.integers(2))
+        dt, sz = (torch.float32, 4) if f32 else (torch.float64, 8)
+        M, N, K = dim(300), dim(300), dim(400)
+        alpha, beta = float(rng.choice([1, -1, 2, 0])), float(rng.choice([1, 0, -1, 2]))
+        (rsa, csa), (rsb, csb) = layout(M, K), layout(K, N)
+        rsc, csc = layout(M, N, sampled_ok=bool(rng.random() < 0.3))
+        if M > 1 and N > 1 and not (rsc >= csc * (N - 1) + 1 or csc >= rsc * (M - 1) + 1):
+            rsc, csc = N + 1, 1
+        off = 5
+        bufA = torch.randint(-3, 4, (off + span(M, K, rsa, csa) + 3,), device=DEV).to(dt)
+        bufB = torch.randint(-3, 4, (off + span(K, N, rsb, csb) + 3,), device=DEV).to(dt)
+        bufC = torch.full((off + span(M, N, rsc, csc) + 3,), float("nan"), dtype=dt, device=DEV)
+        Av = torch.as_strided(bufA, (M, K), (rsa, csa), off)
+        Bv = torch.as_strided(bufB, (K, N), (rsb, csb), off)
+        Cv = torch.as_strided(bufC, (M, N), (rsc, csc), off)
+        C0 = torch.randint(-3, 4, (M, N), device=DEV).to(dt)
+        Cv.copy_(C0)
+        want = alpha * (Av.double() @ Bv.double()) + (beta * C0.double() if beta != 0 else 0)
+        a0, b0 = bufA.clone(), bufB.clone()
+        path = binding.gemm_f64_strided_path(M, N, K, rsa, csa, rsb, csb, rsc, csc)
+        seen[None if path is None else path[0]] += 1
+        fn = binding.gemm_f32_strided if f32 else binding.gemm_f64_strided
+        fn(M, N, K, alpha, bufA.data_ptr() + off * sz, rsa, csa, bufB.data_ptr() + off * sz, rsb, csb, beta,
+           bufC.data_ptr() + off * sz, rsc, csc)
+        torch.cuda.synchronize()
+        what = "case %d: f32=%d %s A%s B%s C%s alpha %g beta %g" % (case, f32, (M, N, K), (rsa, csa), (rsb, csb), (rsc, csc), alpha, beta)
+        assert torch.equal(Cv.double(), want), what
+        assert torch.equal(a0, bufA) and torch.equal(b0, bufB), what + ": A or B written"
+        mask = torch.zeros_like(bufC, dtype=torch.bool)
+        torch.as_strided(mask, (M, N), (rsc, csc), off).fill_(True)
+        assert bool(torch.isnan(bufC[~mask]).all()), what + ": memory outside C's elements written"
+    assert min(seen.values()) >= 20, seen
