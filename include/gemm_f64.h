@@ -160,11 +160,11 @@ int gemm_f64_general_ex(int transa, int transb, int64_t M, int64_t N, int64_t K,
  *
  * Speed: when each operand has a unit stride and its other stride covers the extent (a leading dimension), the
  * call is gemm_f64_general on the same buffers (a column-major C is computed as the transposed problem
- * C^T = B^T A^T, which adds the same products in the same order) and runs on the MFMA kernels at full speed.  When
- * only C is of that kind, A and B are gathered element by element into the same kernels' staging buffers (their
- * register-staged mode: the MFMA loop is the same, the loads are not coalesced).  A C without a unit stride runs an
- * element-wise kernel, one thread per element of C, orders of magnitude slower.  In every case nothing outside the
- * layouts is read or written.  gemm_f64_strided_path tells which of the three a call takes.
+ * C^T = B^T A^T, which adds the same products in the same order) and runs on the MFMA kernels at full speed.  Any
+ * other layout runs on the same kernel in a mode that gathers A and B element by element into its staging buffers
+ * and scatters C (the MFMA loop is the same, the memory accesses are not coalesced; about two thirds of the full
+ * speed for operands sampled with stride 2).  In every case nothing outside the layouts is read or written.
+ * gemm_f64_strided_path tells which of the two a call takes.
  */
 int gemm_f64_strided(int64_t M, int64_t N, int64_t K,
                      double alpha, const double *A, int64_t rsa, int64_t csa,
@@ -177,21 +177,20 @@ int gemm_f64_strided(int64_t M, int64_t N, int64_t K,
  * the choice of kernels per layout is the tuning question of the paper's Section 2.15 Q5 applied to the layout maps
  * of Section 2.9).  Returns
  *   1  the call runs as a call of the transposed signature on the same buffers;
- *   2  it runs on the same MFMA kernels in their register-staged mode, because A or B has no unit stride or no
- *      leading dimension that covers its rows;
- *   0  it runs on the element-wise kernel (C has no unit stride); outputs untouched;
- *  <0  the code gemm_f64_strided would return for these sizes and strides.
- * For 1 and 2 the outputs describe the call as issued.  *swapped = 0: first operand F = A (M x K), second S = B
- * (K x N), C as given.  *swapped = 1: C is column-major and the transposed problem C^T = B^T A^T runs, F = B^T
- * (N x K), S = A^T (K x M).  F(x,k) sits at F[x * *lda + k * *es_a] when *transa == 0 and at F[k * *lda + x * *es_a]
- * when *transa == 1; S(k,x) at S[k * *ldb + x * *es_b] when *transb == 0 and at S[x * *ldb + k * *es_b] when
- * *transb == 1; the row-major output has leading dimension *ldc.  *es_a == *es_b == 1 whenever 1 is returned.
- * Output pointers may be NULL.
+ *   2  it runs on the same MFMA kernel in its sampled mode, because some operand has no unit stride or no leading
+ *      dimension that covers its rows;
+ *  <0  the code gemm_f64_strided would return for these sizes and strides (outputs untouched).
+ * The outputs describe the problem that runs.  *swapped = 0: first operand F = A (M x K), second S = B (K x N),
+ * output O = C (M x N).  *swapped = 1: the transposed problem C^T = B^T A^T runs (C is column-major, or its row
+ * stride is the smaller one): F = B^T (N x K), S = A^T (K x M), O = C^T (N x M).  F(x,k) sits at
+ * F[x * *lda + k * *es_a] when *transa == 0 and at F[k * *lda + x * *es_a] when *transa == 1; S(k,x) at
+ * S[k * *ldb + x * *es_b] when *transb == 0 and at S[x * *ldb + k * *es_b] when *transb == 1; O(r,c) at
+ * O[r * *ldc + c * *es_c].  *es_a == *es_b == *es_c == 1 whenever 1 is returned.  Output pointers may be NULL.
  */
 int gemm_f64_strided_path(int64_t M, int64_t N, int64_t K,
                           int64_t rsa, int64_t csa, int64_t rsb, int64_t csb, int64_t rsc, int64_t csc,
                           int *swapped, int *transa, int *transb, int64_t *lda, int64_t *ldb, int64_t *ldc,
-                          int64_t *es_a, int64_t *es_b);
+                          int64_t *es_a, int64_t *es_b, int64_t *es_c);
 
 /*
  * gemm_f64_general_ws: gemm_f64_general with a workspace on offer (the paper's Section 2.15 Q5 asks how tuning

@@ -86,7 +86,7 @@ def load():
     lib.gemm_f64_device_peak.argtypes = [ip, ip, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.gemm_f64_device_peak.restype = ci
     lp = ctypes.POINTER(i64)
-    lib.gemm_f64_strided_path.argtypes = [i64] * 9 + [ip, ip, ip, lp, lp, lp, lp, lp]
+    lib.gemm_f64_strided_path.argtypes = [i64] * 9 + [ip, ip, ip, lp, lp, lp, lp, lp, lp]
     lib.gemm_f64_strided_path.restype = ci
     lib.gemm_f64_strided.argtypes = [i64, i64, i64, cd, vp, i64, i64, vp, i64, i64, cd, vp, i64, i64, vp]
     lib.gemm_f64_strided.restype = ci
@@ -264,17 +264,14 @@ def gemm_f64_device_peak():
 
 
 def gemm_f64_strided_path(M, N, K, rsa, csa, rsb, csb, rsc, csc):
-    """None when the element-wise kernel would run, else (kind, swapped, transa, transb, lda, ldb, ldc, es_a, es_b) of
-    the call as issued on the tiled kernels (kind 1: transposed signature, 2: register-staged mode); raises for sizes
-    or strides that gemm_f64_strided rejects."""
+    """(kind, swapped, transa, transb, lda, ldb, ldc, es_a, es_b, es_c) of the problem that a strided call runs (kind 1:
+    transposed signature, 2: sampled mode); raises for sizes or strides that gemm_f64_strided rejects."""
     sw, ta, tb = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
-    out = [ctypes.c_int64(0) for _ in range(5)]
+    out = [ctypes.c_int64(0) for _ in range(6)]
     rc = load().gemm_f64_strided_path(M, N, K, rsa, csa, rsb, csb, rsc, csc, ctypes.byref(sw), ctypes.byref(ta), ctypes.byref(tb),
                                       *[ctypes.byref(x) for x in out])
     if rc < 0:
         _check(rc)
-    if rc == 0:
-        return None
     return (rc, bool(sw.value), ta.value, tb.value) + tuple(x.value for x in out)
 
 

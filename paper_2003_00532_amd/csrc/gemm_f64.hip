@@ -114,12 +114,11 @@ extern "C" int gemm_f64_strided(int64_t M, int64_t N, int64_t K, double alpha, c
 
 extern "C" int gemm_f64_strided_path(int64_t M, int64_t N, int64_t K, int64_t rsa, int64_t csa, int64_t rsb, int64_t csb,
                                      int64_t rsc, int64_t csc, int *swapped, int *transa, int *transb, int64_t *lda, int64_t *ldb,
-                                     int64_t *ldc, int64_t *es_a, int64_t *es_b)
+                                     int64_t *ldc, int64_t *es_a, int64_t *es_b, int64_t *es_c)
 {
     const int rc = validate_strides(M, N, K, rsa, csa, rsb, csb, rsc, csc);
     if (rc != GEMM_F64_OK) return rc;
     const StridedPath path = strided_path(M, N, K, rsa, csa, rsb, csb, rsc, csc);
-    if (path.kind == StridedPath::kElementwise) return 0;
     if (swapped) *swapped = path.swapped;
     if (transa) *transa = path.transa;
     if (transb) *transb = path.transb;
@@ -128,6 +127,7 @@ extern "C" int gemm_f64_strided_path(int64_t M, int64_t N, int64_t K, int64_t rs
     if (ldc) *ldc = path.ldc;
     if (es_a) *es_a = path.es_a;
     if (es_b) *es_b = path.es_b;
+    if (es_c) *es_c = path.es_c;
     return (int)path.kind;
 }
 

@@ -179,7 +179,7 @@ struct Job {
     // Sampled operands: elements es.a / es.b apart along the contiguous index, or leading dimensions that do not
     // cover a row; such a job runs in the kSampled mode (64 x 64 tile only) whatever its other properties.
     bool sampled = false;
-    ElemStrides es{1, 1};
+    ElemStrides es{1, 1, 1};
 };
 
 template <typename T, int BM, int BN, int WM, int WN, bool TA, bool TB>
@@ -342,20 +342,19 @@ inline Layout classify(int64_t rows, int64_t cols, int64_t rs, int64_t cs, int64
 // C <- alpha * A B + beta * C with X(r, c) = X[r * rs + c * cs] for each operand (Section 2.9: an operand is an
 // index space plus an affine layout map; Section 2.15 Q4: strides and transposes are such maps).  When every
 // operand has a unit stride the call is the transposed signature (a column-major C is the transposed problem
-// C^T = B^T A^T, which sums the same products in the same order) and runs on the tiled kernels; otherwise the
-// element-wise kernel computes it.  The elements of C must be distinct: one of its strides must span the whole
-// extent of the other.
+// C^T = B^T A^T, which sums the same products in the same order); otherwise the same tiled kernel runs in its
+// kSampled mode.  The elements of C must be distinct: one of its strides must span the whole extent of the other.
 // What a strided call becomes.  kTransposed: the transposed-signature call on the tiled kernels.  kSampled: the tiled
-// kernels in their register-staged mode, because op(A) or op(B) has no unit stride or no leading dimension that
-// covers its rows (es_a / es_b are the element strides along the index the kernel treats as contiguous).
-// kElementwise: C itself has no unit stride.  For the first two, a column-major C means that the transposed
-// problem C^T = B^T A^T is what runs (swapped), and every field describes that call as issued.
+// kernels in their kSampled mode, because some operand has no unit stride or no leading dimension that covers its
+// rows (es_a / es_b / es_c are the element strides along the index the kernel treats as contiguous).  When C is
+// column-major, or its row stride is the smaller one, the transposed problem C^T = B^T A^T is what runs (swapped),
+// and every field describes that call as issued.
 struct StridedPath {
-    enum Kind { kElementwise = 0, kTransposed = 1, kSampled = 2 } kind;
+    enum Kind { kTransposed = 1, kSampled = 2 } kind;
     bool swapped;
     int transa, transb;
     int64_t lda, ldb, ldc;
-    int64_t es_a, es_b;
+    int64_t es_a, es_b, es_c;
 };
 
 // Validation of the strides alone (what needs no pointers), shared by the entry point and the host-side query.
@@ -377,23 +376,27 @@ inline int validate_strides(int64_t M, int64_t N, int64_t K, int64_t rsa, int64_
 inline StridedPath strided_path(int64_t M, int64_t N, int64_t K, int64_t rsa, int64_t csa, int64_t rsb, int64_t csb,
                                 int64_t rsc, int64_t csc)
 {
-    StridedPath p{StridedPath::kElementwise, false, 0, 0, 1, 1, 1, 1, 1};
+    StridedPath p{StridedPath::kSampled, false, 0, 0, 1, 1, 1, 1, 1, 1};
     const Layout lc = classify(M, N, rsc, csc, &p.ldc);
-    if (lc == kNeither) return p;
-    p.swapped = lc == kColumns;
-    // first operand F (rows x K) and second operand S (K x cols) of the row-major problem: A and B, or, for a
-    // column-major C, B^T and A^T (C^T = B^T A^T; transposing an operand swaps its two strides)
+    if (lc == kNeither) {   // the output of the problem that runs sits at O[r * ldc + c * es_c]: columns along the smaller stride
+        p.swapped = rsc < csc;
+        p.ldc = p.swapped ? csc : rsc;
+        p.es_c = p.swapped ? rsc : csc;
+    } else {
+        p.swapped = lc == kColumns;
+    }
+    // first operand F (rows x K) and second operand S (K x cols) of the problem that runs: A and B, or, swapped,
+    // B^T and A^T (C^T = B^T A^T; transposing an operand swaps its two strides)
     const int64_t rows = p.swapped ? N : M, cols = p.swapped ? M : N;
     const int64_t rsf = p.swapped ? csb : rsa, csf = p.swapped ? rsb : csa;
     const int64_t rss = p.swapped ? csa : rsb, css = p.swapped ? rsa : csb;
     const Layout lf = classify(rows, K, rsf, csf, &p.lda), ls = classify(K, cols, rss, css, &p.ldb);
     p.transa = lf == kColumns;
     p.transb = ls == kColumns;
-    if (lf != kNeither && ls != kNeither) {
+    if (lf != kNeither && ls != kNeither && lc != kNeither) {
         p.kind = StridedPath::kTransposed;
         return p;
     }
-    p.kind = StridedPath::kSampled;
     if (lf == kNeither) {   // F(x, k) = F[x * rsf + k * csf]: treat the direction of the smaller stride as contiguous
         p.transa = csf > rsf;
         p.lda = p.transa ? csf : rsf;
@@ -435,16 +438,12 @@ int gemm_strided(const Variant *variants, int count, int64_t M, int64_t N, int64
         if (beta == T(1)) return GEMM_F64_OK;
         return launch_scale<T>(m, n, beta, C, rsc, csc, stream) == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
     }
-    if (path.kind == StridedPath::kSampled) {
-        Job<T> job{path.transa, path.transb, (int)rows, (int)cols, k, alpha, F, path.lda, S, path.ldb, beta, C, path.ldc, stream,
-                   1, SplitK{k, 0, 0, 0}};
-        job.sampled = true;
-        job.es = ElemStrides{path.es_a, path.es_b};
-        return launch_mfma<T, 64, 64, 2, 2>(job) == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
-    }
-    const dim3 grid((unsigned)ceil_div(M * N, 256)), block(256);
-    hipLaunchKernelGGL(gemm_naive_kernel<T>, grid, block, 0, stream, m, n, k, alpha, A, rsa, csa, B, rsb, csb, beta, C, rsc, csc);
-    return hipGetLastError() == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
+    // kSampled: the 64 x 64 tile, the only one the mode is built for
+    Job<T> job{path.transa, path.transb, (int)rows, (int)cols, k, alpha, F, path.lda, S, path.ldb, beta, C, path.ldc, stream, 1,
+               SplitK{k, 0, 0, 0}};
+    job.sampled = true;
+    job.es = ElemStrides{path.es_a, path.es_b, path.es_c};
+    return launch_mfma<T, 64, 64, 2, 2>(job) == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
 }
 
 }  // namespace gemm_detail

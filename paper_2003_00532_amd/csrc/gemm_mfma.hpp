@@ -72,10 +72,10 @@ struct SplitK {
     int64_t step_a, step_b, step_c;
 };
 
-// Elements between neighbours along the contiguous index of op(A) and op(B); read by the kSampled mode only
-// (1 everywhere else).
+// Elements between neighbours along the contiguous index of op(A) and op(B) and along the rows of C; read by the
+// kSampled mode only (1 everywhere else).
 struct ElemStrides {
-    int64_t a, b;
+    int64_t a, b, c;
 };
 
 // Workgroup id -> tile coordinates.  Block b runs on XCD b % kXcds.  Each XCD receives a
@@ -366,8 +366,8 @@ struct Panel {
 // addresses memory with 64-bit pointers and is what remains for leading dimensions too large for the
 // 32-bit lane offsets of the asynchronous copies.
 // MODE = kSampled is kStaged for operands whose elements are `es` apart along their contiguous index (a matrix
-// sampled with a stride in both directions); it is the only mode that reads `es`, and costs a few more
-// registers, so it is built for the 64 x 64 tile only.
+// sampled with a stride in both directions), C included; it is the only mode that reads `es`, and costs a
+// few more registers, so it is built for the 64 x 64 tile only.
 // (Asking the compiler for more than two waves per SIMD was measured to cost 3 to 25 % on the larger
 // tiles: it then schedules the K loop differently; the smaller tiles fit more waves anyway.)
 template <typename T, int BM, int BN, int WM, int WN, int MODE, bool TA, bool TB>
@@ -556,7 +556,8 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, i
     constexpr int ROW_STEP = EL::d_row(1, 0) - EL::d_row(0, 0);   // 4 for double, 1 for float
     static_assert(EL::d_row(2, 0) - EL::d_row(1, 0) == ROW_STEP && EL::d_row(3, 0) - EL::d_row(2, 0) == ROW_STEP, "");
     constexpr int MB = (MI >= 2) ? 2 : 1;
-    T *const c_lane = C + (int64_t)row_base * ldc + col_base;
+    const int64_t cs_c = SAMPLED ? es.c : 1;   // elements between neighbouring columns of C
+    T *const c_lane = C + (int64_t)row_base * ldc + col_base * cs_c;
     const int64_t r_step = (int64_t)ROW_STEP * ldc, mi_step = 16 * ldc;
     // Three forms, chosen once per workgroup: alpha = beta = 1 (the paper's own operation: one addition
     // per element), beta = 0 (C is not read) and the general one.
@@ -579,7 +580,7 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, i
 #pragma unroll
                     for (int ni = 0; ni < NI; ++ni) {
                         const int col = col_base + ni * 16;
-                        if (read_c && (!GENERIC || tile_full || (row < M && col < N))) cin[mi - mb][ni][r] = c_r[ni * 16];
+                        if (read_c && (!GENERIC || tile_full || (row < M && col < N))) cin[mi - mb][ni][r] = c_r[ni * 16 * cs_c];
                         else cin[mi - mb][ni][r] = T(0);
                     }
                     c_r += r_step;
@@ -597,7 +598,7 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, i
                     for (int ni = 0; ni < NI; ++ni) {
                         const int col = col_base + ni * 16;
                         if (!GENERIC || tile_full || (row < M && col < N))
-                            c_r[ni * 16] = UNIT ? cin[mi - mb][ni][r] + acc[mi][ni][r]
+                            c_r[ni * 16 * cs_c] = UNIT ? cin[mi - mb][ni][r] + acc[mi][ni][r]
                                                 : scaled_update(alpha, acc[mi][ni][r], beta, cin[mi - mb][ni][r], read_c);
                     }
                     c_r += r_step;
@@ -616,7 +617,7 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, i
 // Kept as the bottom rung of the ladder (the paper's Section 2.3 starting point), as an
 // on-device cross-check that shares nothing with the MFMA kernel, and, since every operand is
 // addressed through a row stride and a column stride (X(r, c) = X[r * rs + c * cs], the affine layout
-// maps of Section 2.9), as the path for layouts in which no stride is 1.
+// maps of Section 2.9), for any layout.
 template <typename T>
 __global__ void __launch_bounds__(256)
 gemm_naive_kernel(int M, int N, int K, T alpha, const T *__restrict__ A, int64_t rsa, int64_t csa, const T *__restrict__ B,

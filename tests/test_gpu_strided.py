@@ -136,8 +136,8 @@ def test_unit_stride_layouts_over_several_tiles(gpu_device, kind, dtype):
 @pytest.mark.parametrize("dtype", DTYPES, ids=["f64", "f32"])
 @pytest.mark.parametrize("kind", ["int", "uniform"])
 def test_sampled_layouts(gpu_device, kind, dtype):
-    # sampled A or B with a unit-stride C run on the tiled kernels (gathered into the staging buffers), a sampled C
-    # on the element-wise kernel
+    # operands without a unit stride run on the tiled kernel's sampled mode: A and B gathered into the staging
+    # buffers, C scattered
     t = 0
     for (M, N, K) in [(70, 50, 90), (33, 129, 64), (150, 7, 40), (200, 264, 150)]:
         A, B, C0 = _operands(200 + t, M, N, K, kind, dtype)
@@ -151,7 +151,7 @@ def test_sampled_layouts(gpu_device, kind, dtype):
 
 def test_the_path_rule_agrees_with_what_the_tests_above_assume():
     assert binding.gemm_f64_strided_path(70, 50, 90, 2 * 90 + 5, 2, 52, 1, 52, 1)[0] == 2       # row_step2, row, row
-    assert binding.gemm_f64_strided_path(70, 50, 90, 92, 1, 52, 1, 2 * 50 + 5, 2) is None       # row, row, row_step2
+    assert binding.gemm_f64_strided_path(70, 50, 90, 92, 1, 52, 1, 2 * 50 + 5, 2)[0] == 2       # row, row, row_step2
     assert binding.gemm_f64_strided_path(70, 50, 90, 92, 1, 1, 93, 1, 73)[0] == 1               # row, col, col
 
 
@@ -224,7 +224,8 @@ def test_seeded_random_layouts_match_the_exact_integer_product(gpu_device):
                 (int(rng.integers(1, 4)), int(rng.integers(1, 4))), (s * (cols + pad), 1)][kind]
 
     span = lambda r, c, rs, cs: (max(r, 1) - 1) * rs + (max(c, 1) - 1) * cs + 1
-    seen = {None: 0, 1: 0, 2: 0}
+    seen = {1: 0, 2: 0}
+    sampled_c = 0
     for case in range(400):
         f32 = bool(rng.integers(2))
         dt, sz = (torch.float32, 4) if f32 else (torch.float64, 8)
@@ -246,7 +247,8 @@ def test_seeded_random_layouts_match_the_exact_integer_product(gpu_device):
         want = alpha * (Av.double() @ Bv.double()) + (beta * C0.double() if beta != 0 else 0)
         a0, b0 = bufA.clone(), bufB.clone()
         path = binding.gemm_f64_strided_path(M, N, K, rsa, csa, rsb, csb, rsc, csc)
-        seen[None if path is None else path[0]] += 1
+        seen[path[0]] += 1
+        sampled_c += path[9] != 1
         fn = binding.gemm_f32_strided if f32 else binding.gemm_f64_strided
         fn(M, N, K, alpha, bufA.data_ptr() + off * sz, rsa, csa, bufB.data_ptr() + off * sz, rsb, csb, beta,
            bufC.data_ptr() + off * sz, rsc, csc)
@@ -257,4 +259,4 @@ def test_seeded_random_layouts_match_the_exact_integer_product(gpu_device):
         mask = torch.zeros_like(bufC, dtype=torch.bool)
         torch.as_strided(mask, (M, N), (rsc, csc), off).fill_(True)
         assert bool(torch.isnan(bufC[~mask]).all()), what + ": memory outside C's elements written"
-    assert min(seen.values()) >= 20, seen
+    assert min(seen.values()) >= 20 and sampled_c >= 20, (seen, sampled_c)

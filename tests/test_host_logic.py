@@ -200,13 +200,13 @@ def test_strided_entry_points_validate_strides_before_any_launch():
 
 
 def test_strided_path_addresses_the_same_elements_as_the_strides():
-    # whenever the rule maps a strided call onto the tiled kernels, every element of every operand must sit at the
-    # address the strides give; the transposed signature is claimed exactly when all three operands have a
-    # unit-stride description, the element-wise kernel exactly when C has none
+    # the problem that the rule says will run must address, element by element, exactly what the strides address;
+    # the transposed signature is claimed exactly when all three operands have a unit-stride description
     import itertools
     import numpy as np
     rng = np.random.default_rng(0)
-    counts = {0: 0, 1: 0, 2: 0}
+    counts = {1: 0, 2: 0}
+    sampled_c = 0
 
     def unit(rows, cols, rs, cs):
         return ((cs == 1 or cols == 1) and (rs >= cols or rows == 1)) or ((rs == 1 or rows == 1) and (cs >= rows or cols == 1))
@@ -214,11 +214,12 @@ def test_strided_path_addresses_the_same_elements_as_the_strides():
     for M, N, K in itertools.product([1, 2, 3, 5], repeat=3):
         for _ in range(60):
             def pick(rows, cols):
-                kind = rng.integers(5)
+                kind = rng.integers(6)
                 if kind == 0: return (cols + int(rng.integers(3)), 1)          # row-major, maybe padded
                 if kind == 1: return (1, rows + int(rng.integers(3)))          # column-major, maybe padded
-                if kind == 2: return (2 * cols + 1, 2)                         # sampled
-                if kind == 3: return (1, 1)                                    # overlapping unless a vector
+                if kind == 2: return (2 * cols + 1, 2)                         # sampled rows
+                if kind == 3: return (3, 3 * rows + 2)                         # sampled columns
+                if kind == 4: return (1, 1)                                    # overlapping unless a vector
                 return (int(rng.integers(1, 9)), int(rng.integers(1, 9)))
             (rsa, csa), (rsb, csb), (rsc, csc) = pick(M, K), pick(K, N), pick(M, N)
             try:
@@ -233,36 +234,32 @@ def test_strided_path_addresses_the_same_elements_as_the_strides():
             b_addr = k[:, None] * rsb + j * csb
             c_addr = i * rsc + j * csc
             assert len(set(c_addr.ravel().tolist())) == M * N, "accepted a C whose elements overlap"
-            if path is None:
-                counts[0] += 1
-                assert not unit(M, N, rsc, csc)
-                continue
-            kind, swapped, ta, tb, lda, ldb, ldc, es_a, es_b = path
+            kind, swapped, ta, tb, lda, ldb, ldc, es_a, es_b, es_c = path
             counts[kind] += 1
-            assert unit(M, N, rsc, csc)
-            all_unit = unit(M, K, rsa, csa) and unit(K, N, rsb, csb)
+            sampled_c += not unit(M, N, rsc, csc)
+            all_unit = unit(M, K, rsa, csa) and unit(K, N, rsb, csb) and unit(M, N, rsc, csc)
             assert (kind == 1) == all_unit
-            if kind == 1:
-                assert es_a == 1 and es_b == 1
             rows, cols = (N, M) if swapped else (M, N)
             x_f, x_s, kk = np.arange(rows)[:, None], np.arange(cols)[None, :], np.arange(K)
             f_addr = kk[None, :] * lda + x_f * es_a if ta else x_f * lda + kk[None, :] * es_a      # F(x, k), rows x K
             s_addr = x_s * ldb + kk[:, None] * es_b if tb else kk[:, None] * ldb + x_s * es_b      # S(k, x), K x cols
-            o_addr = np.arange(rows)[:, None] * ldc + np.arange(cols)[None, :]
+            o_addr = np.arange(rows)[:, None] * ldc + np.arange(cols)[None, :] * es_c
             if kind == 1:   # a legal call of the transposed signature
-                assert lda >= max(1, rows if ta else K) and ldb >= max(1, K if tb else cols)
-            assert ldc >= max(1, cols)
+                assert (es_a, es_b, es_c) == (1, 1, 1)
+                assert lda >= max(1, rows if ta else K) and ldb >= max(1, K if tb else cols) and ldc >= max(1, cols)
             if not swapped:
                 assert np.array_equal(f_addr, a_addr) and np.array_equal(s_addr, b_addr) and np.array_equal(o_addr, c_addr)
             else:
                 assert np.array_equal(f_addr, b_addr.T) and np.array_equal(s_addr, a_addr.T) and np.array_equal(o_addr, c_addr.T)
-    assert min(counts.values()) > 200, counts
+    assert min(counts.values()) > 200 and sampled_c > 200, (counts, sampled_c)
     # the conventional cases by name
-    assert binding.gemm_f64_strided_path(100, 80, 60, 60, 1, 80, 1, 80, 1) == (1, False, 0, 0, 60, 80, 80, 1, 1)      # all row-major
-    assert binding.gemm_f64_strided_path(100, 80, 60, 1, 100, 1, 60, 1, 100) == (1, True, 0, 0, 60, 100, 100, 1, 1)   # all column-major
-    assert binding.gemm_f64_strided_path(100, 80, 60, 1, 100, 80, 1, 80, 1) == (1, False, 1, 0, 100, 80, 80, 1, 1)    # A^T B
-    assert binding.gemm_f64_strided_path(100, 80, 60, 128, 2, 80, 1, 80, 1) == (2, False, 0, 0, 128, 80, 80, 2, 1)    # sampled A
-    assert binding.gemm_f64_strided_path(100, 80, 60, 60, 1, 80, 1, 2 * 80, 2) is None                                 # sampled C
+    path = binding.gemm_f64_strided_path
+    assert path(100, 80, 60, 60, 1, 80, 1, 80, 1) == (1, False, 0, 0, 60, 80, 80, 1, 1, 1)          # all row-major
+    assert path(100, 80, 60, 1, 100, 1, 60, 1, 100) == (1, True, 0, 0, 60, 100, 100, 1, 1, 1)       # all column-major
+    assert path(100, 80, 60, 1, 100, 80, 1, 80, 1) == (1, False, 1, 0, 100, 80, 80, 1, 1, 1)        # A^T B
+    assert path(100, 80, 60, 128, 2, 80, 1, 80, 1) == (2, False, 0, 0, 128, 80, 80, 2, 1, 1)        # sampled A
+    assert path(100, 80, 60, 60, 1, 80, 1, 2 * 80, 2) == (2, False, 0, 0, 60, 80, 160, 1, 1, 2)     # sampled C
+    assert path(100, 80, 60, 60, 1, 80, 1, 2, 2 * 100) == (2, True, 1, 1, 80, 60, 200, 1, 1, 2)     # sampled column-major C
 
 
 def test_device_peak_query_fails_cleanly_without_a_device():
