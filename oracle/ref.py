@@ -130,7 +130,8 @@ def gemm_general_ref(transa, transb, alpha, A, B, beta, C):
 
 def general_scale(transa, transb, alpha, A, B, beta, C0):
     """float64 S = |alpha| * |op(A)| @ |op(B)| + |beta * C0|: the scale of the elementwise tolerance of the
-    general operation, obtained by running the binary64 oracle on absolute values."""
+    general operation, obtained by running the binary64 oracle on absolute values (C0 is ignored when beta == 0).
+    Pinned against exact rational arithmetic by tests/test_oracle_scale_pins.py."""
     S = np.abs(C0.astype(np.float64))
     if beta == 0:
         S = np.zeros(C0.shape, dtype=np.float64)  # C0 is not read then and may hold NaN

@@ -83,9 +83,9 @@ def test_pins_of_the_transposed_signature_through_strides_on_the_device(gpu_devi
 
 
 def _scale(alpha, A, B, beta, C0):
-    S = np.abs(C0.astype(np.float64)) * abs(float(beta)) if beta != 0 else np.zeros(C0.shape)
-    oracle.gemm_strided_ref(abs(float(alpha)), np.abs(A.astype(np.float64)), np.abs(B.astype(np.float64)), 1.0, S)
-    return S
+    # A, B, C0 are the logical operands (dense, row-major), so the scale of the strided operation is that of the
+    # plain signature: the routine pinned by tests/test_oracle_scale_pins.py
+    return oracle.general_scale(0, 0, alpha, A, B, beta, C0)
 
 
 def _operands(seed, M, N, K, kind, dtype):
