@@ -88,16 +88,19 @@ int gemm_f64_ref_ijk(int64_t M, int64_t N, int64_t K, const double *A,
 {
     int rc = check_args(M, N, K, A, lda, B, ldb, C, ldc);
     if (rc) return rc;
-    for (int64_t i = 0; i < M; ++i)
-        for (int64_t j = 0; j < N; ++j)
+    /* one running value per element: it starts from C, takes the K rounded products in ascending k, each
+       addition rounded, and is stored once */
+    for (int64_t i = 0; i < M; ++i) {
+        const double *arow = A + i * lda;
+        for (int64_t j = 0; j < N; ++j) {
+            double acc = C[i * ldc + j];
             for (int64_t k = 0; k < K; ++k) {
-                double a = A[i * lda + k];
-                double b = B[k * ldb + j];
-                double ci = C[i * ldc + j];
-                double p = a * b;
-                double co = ci + p;
-                C[i * ldc + j] = co;
+                const double term = arow[k] * B[k * ldb + j];
+                acc = acc + term;
             }
+            C[i * ldc + j] = acc;
+        }
+    }
     return 0;
 }
 
@@ -122,6 +125,16 @@ int gemm_f64_absref(int64_t M, int64_t N, int64_t K, const double *A,
         }
     }
     return 0;
+}
+
+/* Digest of the sources and flags this library was built from (set by oracle/build.py). */
+#ifndef ORACLE_BUILD_ID
+#define ORACLE_BUILD_ID "unknown"
+#endif
+const char *oracle_build_id(void)
+{
+    static const char tagged[] = "oracle-build-id:" ORACLE_BUILD_ID;
+    return tagged + sizeof("oracle-build-id:") - 1;
 }
 
 /* Number of threads an OpenMP region of this library will use right now. */

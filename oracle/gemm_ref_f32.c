@@ -67,16 +67,17 @@ int gemm_f32_ref_ijk(int64_t M, int64_t N, int64_t K, const float *A, int64_t ld
 {
     int rc = check_args32(M, N, K, A, lda, B, ldb, C, ldc);
     if (rc) return rc;
-    for (int64_t i = 0; i < M; ++i)
-        for (int64_t j = 0; j < N; ++j)
+    for (int64_t i = 0; i < M; ++i) {
+        const float *arow = A + i * lda;
+        for (int64_t j = 0; j < N; ++j) {
+            float acc = C[i * ldc + j];
             for (int64_t k = 0; k < K; ++k) {
-                float a = A[i * lda + k];
-                float b = B[k * ldb + j];
-                float ci = C[i * ldc + j];
-                float p = a * b;
-                float co = ci + p;
-                C[i * ldc + j] = co;
+                const float term = arow[k] * B[k * ldb + j];
+                acc = acc + term;
             }
+            C[i * ldc + j] = acc;
+        }
+    }
     return 0;
 }
 
