@@ -27,14 +27,37 @@ PEAK_FP64_MFMA_TFLOPS = 78.6   # MI355X published dense FP64 matrix peak (256 CU
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X published dense FP32 matrix peak
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), scaled
-# by the copy-kernel calibration; None until measured for that workload.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/dgemm_mfma_128x128x16_c3_8192_pmc.txt: FETCH_SIZE 6 633 980 KiB x 2.0 + WRITE_SIZE 524 288 KiB x 1.0
-    ("c3_8192", "mfma_128x128x16"): (6633980 * 2.0 + 524288 * 1.0) * 1024,
-    # profiles/sgemm_mfma_128x128x32_c3_8192_pmc.txt: FETCH_SIZE 3 307 360 KiB x 2.0 + WRITE_SIZE 262 228 KiB x 1.0
-    ("c3_8192", "mfma_128x128x32"): (3307360 * 2.0 + 262228 * 1.0) * 1024,
+# The paper's own framing (context, not the target): its machine, the peak it prices against and its best result.
+PAPER_CONTEXT = {
+    "machine": "one core of an Intel Core i7-8700K (AVX-2, two FMA units, 4.7 GHz turbo), fp64",
+    "peak_gflops_per_core": 75.2,            # Section 1.2
+    "best_gflops": 61.94,                    # Section 2.10: 82 % of that peak, within 9 % of MKL / OpenBLAS
+    "naive_gflops": [0.47, 4.53],            # Section 1.3: clang -O3 and gcc -O3 on the plain nest
+    "workload": "C += A*B, M = 2088, N = K = 2048, row-major, single thread",
+    "note": "another machine and another kind of hardware: context only, never a baseline for vs_baseline",
 }
+
+
+def traffic_from_profile(prec_letter, vname, wname, current_build_id):
+    """HBM bytes per launch from the tracked rocprofv3 --pmc summary of this kernel and workload, if there is one.
+
+    The summary (profiles/<s|d>gemm_<variant>_<workload>_pmc.txt) records FETCH_SIZE and WRITE_SIZE per dispatch,
+    the copy-kernel scaling, the resulting bytes (a line `traffic_bytes_per_launch = N`) and the build id of the
+    library it was taken with (`library_build_id = X`).  Returns (bytes or None, description of the source)."""
+    import re
+    path = os.path.join(ROOT, "profiles", "%sgemm_%s_%s_pmc.txt" % (prec_letter, vname, wname))
+    if not os.path.exists(path):
+        return None, None
+    text = open(path).read()
+    m = re.search(r"^traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", text, re.M)
+    b = re.search(r"^library_build_id\s*=\s*(\S+)", text, re.M)
+    if not m:
+        return None, None
+    prof_id = b.group(1) if b else None
+    return float(m.group(1)), {"file": os.path.relpath(path, ROOT), "profile_build_id": prof_id,
+                               "current_build_id": current_build_id, "same_build": prof_id == current_build_id,
+                               "what": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per dispatch, scaled by a plain copy; "
+                                       "taken in a separate run, not in this one"}
 
 
 def log(*a):
@@ -92,6 +115,59 @@ def copy_calibration():
     print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "copies": 5}))
 
 
+def time_launches(call, stream, launches):
+    """Per-launch durations from HIP events recorded on the launch stream between consecutive launches (ms), and the
+    duration per launch of the same number of launches back to back with one event on either side."""
+    import torch
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(launches + 1)]
+    torch.cuda.synchronize()
+    events[0].record(stream)
+    for i in range(launches):
+        call()
+        events[i + 1].record(stream)
+    torch.cuda.synchronize()
+    sep = [events[i].elapsed_time(events[i + 1]) for i in range(launches)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(launches):
+        call()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return sep, e0.elapsed_time(e1) / launches
+
+
+OTHER_WORKLOADS = (("c0_256", 200), ("c1_2048", 50), ("c2_edge", 50), ("c4_rankk", 20))
+
+
+def other_workloads(gemm_ex, choose, variant_name, np_dtype, peak, seed, stream, cus, skip):
+    """The configurations that are not the headline: a handful of launches each of the automatic variant, inputs
+    generated on the device by the same counter-based generator (same bits as the host one), timed both ways."""
+    import torch
+    from paper_2003_00532_amd import synth
+    out = {}
+    for name, launches in OTHER_WORKLOADS:
+        if name == skip:
+            continue
+        w = synth.WORKLOADS[name]
+        dA, dB, dC = synth.device_workload_inputs(w, seed=seed, dtype=np_dtype)
+
+        def call():
+            gemm_ex(w.M, w.N, w.K, dA, w.lda, dB, w.ldb, dC, w.ldc, stream=stream, variant=-1)
+
+        for _ in range(3):
+            call()
+        sep, b2b = time_launches(call, stream, launches)
+        ms = sum(sep) / len(sep)
+        out[name] = {"kernel_variant": variant_name(choose(w.M, w.N, w.K, cus)), "launches": launches,
+                     "kernel_ms": round(ms, 5), "kernel_ms_min": round(min(sep), 5),
+                     "tflops": round(w.flops / (ms * 1e-3) / 1e12, 3), "frac": round(w.flops / (ms * 1e-3) / 1e12 / peak, 4),
+                     "back_to_back_ms": round(b2b, 5), "back_to_back_tflops": round(w.flops / (b2b * 1e-3) / 1e12, 3),
+                     "back_to_back_frac": round(w.flops / (b2b * 1e-3) / 1e12 / peak, 4)}
+        log("%s: %s" % (name, json.dumps(out[name])))
+        del dA, dB, dC
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -102,6 +178,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--dtype", choices=["f64", "f32"], default="f64")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short timings of the configurations that are not the headline")
     ap.add_argument("--copy-calibration", action="store_true")
     ap.add_argument("--compare-vendor", action="store_true",
                     help="after the measurement, time the vendor BLAS behind torch.addmm on the same buffers (context only)")
@@ -138,9 +216,7 @@ def main():
     w = synth.WORKLOADS[args.workload]
     dev = torch.device("cuda:0")
     t0 = time.perf_counter()
-    Ab, Bb, Cb = synth.workload_inputs(w, seed=args.seed, dtype=np_dtype)
-    dA, dB, dC = (torch.from_numpy(x).to(dev) for x in (Ab, Bb, Cb))
-    del Ab, Bb, Cb
+    dA, dB, dC = synth.device_workload_inputs(w, seed=args.seed, dtype=np_dtype, device=dev)
     torch.cuda.synchronize()
     log("inputs for %s generated and resident in HBM after %.1f s" % (w.name, time.perf_counter() - t0))
 
@@ -175,7 +251,7 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     gflops = w.flops / (ms_per_step * 1e-3) / 1e9
     achieved_tflops = w.flops / (kernel_ms * 1e-3) / 1e12
-    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, vname))
+    traffic, traffic_source = traffic_from_profile("s" if f32 else "d", vname, w.name, binding.gemm_f64_build_id())
     alg_bytes = w.algorithmic_bytes * elem / 8.0
     prec = "fp32" if f32 else "fp64"
 
@@ -198,7 +274,7 @@ def main():
         "pct_of_%s_mfma_peak" % prec: round(100.0 * gflops / (peak * 1e3), 2),
         "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved_tflops / peak, 4),
-                     "traffic": traffic, "kernel_ms": round(kernel_ms, 4),
+                     "traffic": traffic, "traffic_source": traffic_source, "kernel_ms": round(kernel_ms, 4),
                      "kernel_ms_min": round(min(per_launch_ms), 4), "kernel_ms_median": round(kernel_ms_median, 4),
                      "kernel_ms_max": round(max(per_launch_ms), 4),
                      "algorithmic_flops_per_launch": w.flops, "algorithmic_bytes_per_launch": alg_bytes},
@@ -265,6 +341,11 @@ def main():
                                           "ms_per_call": round(vms, 4), "what": "torch.addmm on the same buffers, comparison only"}
         else:
             out["vendor_blas_context"] = None
+    out["paper_context"] = PAPER_CONTEXT
+    if not args.no_other_workloads:
+        del dA, dB, dC
+        out["other_workloads"] = other_workloads(gemm_ex, choose, variant_name, np_dtype, peak, args.seed, stream,
+                                                 props.multi_processor_count, w.name)
     if not args.no_cpu_baseline:
         t0 = time.perf_counter()
         out["cpu_baseline"] = cpu_baseline(w, args.seed, np_dtype=np_dtype)

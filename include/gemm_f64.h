@@ -33,7 +33,7 @@ enum {
     GEMM_F64_ERR_NULL = -5,      /* null pointer for an operand that has elements        */
     GEMM_F64_ERR_ALIGN = -6,     /* a pointer is not 8-byte aligned                      */
     GEMM_F64_ERR_LAUNCH = -7,    /* the HIP runtime refused the launch (see hipGetLastError) */
-    GEMM_F64_ERR_TOO_LARGE = -8, /* M, N or K above 2^31 - 1                             */
+    GEMM_F64_ERR_TOO_LARGE = -8, /* M, N or K above 2^31 - 129 (32-bit tile arithmetic)     */
     GEMM_F64_ERR_VARIANT = -9    /* unknown kernel variant index                         */
 };
 
@@ -291,6 +291,13 @@ const char *gemm_f64_strerror(int code);
 
 /* Library version: major * 10000 + minor * 100 + patch. */
 int gemm_f64_version(void);
+
+/*
+ * A digest of the sources and compiler flags the library was built from (hexadecimal, static, never NULL; "unknown"
+ * when the build did not provide one).  The build script compares it with the digest of the sources on disk to decide
+ * whether a built library is out of date, independently of file times.
+ */
+const char *gemm_f64_build_id(void);
 
 #ifdef __cplusplus
 }

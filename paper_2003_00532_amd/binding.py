@@ -29,6 +29,13 @@ def load():
         raise FileNotFoundError(
             "%s not found: the HIP library is not built (run `python -c 'import __graft_entry__ as g; g.build()'`); "
             "there is no CPU fallback" % LIB_PATH)
+    # PyTorch ships its own copy of the HIP runtime.  When it is present it must be loaded first, so that this
+    # library binds to the same runtime as the tensors and streams it is handed; two runtimes in one process do not
+    # share streams or loaded kernels, and launches fail.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(LIB_PATH)
     i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
     lib.gemm_f64.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
@@ -47,6 +54,8 @@ def load():
     lib.gemm_f64_strerror.restype = ctypes.c_char_p
     lib.gemm_f64_version.argtypes = []
     lib.gemm_f64_version.restype = ci
+    lib.gemm_f64_build_id.argtypes = []
+    lib.gemm_f64_build_id.restype = ctypes.c_char_p
     lib.gemm_f32.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
     lib.gemm_f32.restype = ci
     lib.gemm_f32_ex.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, ci]
@@ -166,6 +175,10 @@ def gemm_f64_tile_of_block(block, tiles_m, tiles_n):
 
 def gemm_f64_version() -> int:
     return int(load().gemm_f64_version())
+
+
+def gemm_f64_build_id() -> str:
+    return load().gemm_f64_build_id().decode()
 
 
 # ---- single precision (include/gemm_f32.h) ------------------------------------------------------

@@ -17,11 +17,21 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 
+def source_digest() -> str:
+    """SHA-256 over the compiler flags and the contents of every file the library is built from."""
+    import hashlib
+    h = hashlib.sha256(" ".join(FLAGS).encode())
+    for p in DEPENDS:
+        with open(p, "rb") as f:
+            h.update(os.path.basename(p).encode() + b"\0" + f.read())
+    return h.hexdigest()[:32]
+
+
 def build(verbose: bool = False) -> str:
     """Compile every source to an object (in parallel: one hipcc per file) and link them into the library."""
     from concurrent.futures import ThreadPoolExecutor
     noise = "is not a recognized feature for this target"
-    compile_flags = [f for f in FLAGS if f != "-shared"]
+    compile_flags = [f for f in FLAGS if f != "-shared"] + ['-DGEMM_BUILD_ID="%s"' % source_digest()]
 
     def compile_one(src):
         obj = os.path.join(HERE, os.path.basename(src) + ".%d.o" % os.getpid())
@@ -50,11 +60,22 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
-def is_stale() -> bool:
+def built_digest():
+    """The digest stored in the built library, or None when there is no library or it carries none.  Read from the
+    file's bytes (the library holds the text "gemm-build-id:<digest>"), not by loading it: loading would pull in the
+    system HIP runtime before PyTorch has loaded its own."""
+    import re
     if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(p) > t for p in DEPENDS)
+        return None
+    with open(LIB, "rb") as f:
+        m = re.search(rb"gemm-build-id:([0-9a-f]{32})", f.read())
+    return m.group(1).decode() if m else None
+
+
+def is_stale() -> bool:
+    """True when there is no library or it was built from other sources or flags than the ones on disk (file times
+    play no part: they do not survive every way a tree is copied)."""
+    return built_digest() != source_digest()
 
 
 if __name__ == "__main__":

@@ -84,7 +84,7 @@ extern "C" int gemm_f32_split_k_plan(int transa, int transb, int64_t M, int64_t 
 {
     if ((transa != 0 && transa != 1) || (transb != 0 && transb != 1) || M < 0 || N < 0 || K < 0 || workspace_bytes < 0)
         return GEMM_F64_ERR_DIM;
-    if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
+    if (M > kMaxExtent || N > kMaxExtent || K > kMaxExtent) return GEMM_F64_ERR_TOO_LARGE;
     const Plan plan = plan_split_k(kVariants, kNumVariants, transa, transb, M, N, K, num_cu, (int)sizeof(float), workspace_bytes);
     if (variant) *variant = plan.variant;
     if (splits) *splits = plan.splits;

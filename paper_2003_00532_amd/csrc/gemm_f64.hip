@@ -57,13 +57,23 @@ extern "C" const char *gemm_f64_strerror(int code)
     case GEMM_F64_ERR_NULL: return "null pointer for a non-empty operand";
     case GEMM_F64_ERR_ALIGN: return "pointer not aligned to the element size";
     case GEMM_F64_ERR_LAUNCH: return "HIP kernel launch failed";
-    case GEMM_F64_ERR_TOO_LARGE: return "dimension exceeds 2^31 - 1";
+    case GEMM_F64_ERR_TOO_LARGE: return "dimension exceeds 2^31 - 129";
     case GEMM_F64_ERR_VARIANT: return "unknown kernel variant";
     default: return "unknown error code";
     }
 }
 
-extern "C" int gemm_f64_version(void) { return 400; }
+extern "C" int gemm_f64_version(void) { return 500; }
+
+#ifndef GEMM_BUILD_ID
+#define GEMM_BUILD_ID "unknown"
+#endif
+extern "C" const char *gemm_f64_build_id(void)
+{
+    // the prefix lets the build script find the digest in the file without loading the library
+    static const char tagged[] = "gemm-build-id:" GEMM_BUILD_ID;
+    return tagged + sizeof("gemm-build-id:") - 1;
+}
 
 extern "C" int gemm_f64_choose_variant_general(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu)
 {
@@ -136,7 +146,7 @@ extern "C" int gemm_f64_split_k_plan(int transa, int transb, int64_t M, int64_t 
 {
     if ((transa != 0 && transa != 1) || (transb != 0 && transb != 1) || M < 0 || N < 0 || K < 0 || workspace_bytes < 0)
         return GEMM_F64_ERR_DIM;
-    if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
+    if (M > kMaxExtent || N > kMaxExtent || K > kMaxExtent) return GEMM_F64_ERR_TOO_LARGE;
     const Plan plan = plan_split_k(kVariants, kNumVariants, transa, transb, M, N, K, num_cu, (int)sizeof(double), workspace_bytes);
     if (variant) *variant = plan.variant;
     if (splits) *splits = plan.splits;

@@ -125,6 +125,10 @@ inline Plan plan_split_k(const Variant *variants, int count, int transa, int tra
     return best;
 }
 
+// The kernels hold extents and tile origins in 32-bit integers and form "origin + tile size" and "extent + stage
+// depth - 1" in them; the largest tile is 128 wide and the deepest stage 32, so extents up to 2^31 - 1 - 128 are safe.
+constexpr int64_t kMaxExtent = (int64_t)INT32_MAX - 128;
+
 // Stored shapes: A is M x K (K x M when transa), B is K x N (N x K when transb), C is M x N; a leading
 // dimension must cover the stored row.  A and B are only required when the product is formed
 // (ab_read: alpha != 0 and K > 0).
@@ -134,7 +138,7 @@ int validate(int transa, int transb, int64_t M, int64_t N, int64_t K, bool ab_re
 {
     if (M < 0 || N < 0 || K < 0) return GEMM_F64_ERR_DIM;
     if ((transa != 0 && transa != 1) || (transb != 0 && transb != 1)) return GEMM_F64_ERR_DIM;
-    if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
+    if (M > kMaxExtent || N > kMaxExtent || K > kMaxExtent) return GEMM_F64_ERR_TOO_LARGE;
     const int64_t a_width = transa ? M : K, b_width = transb ? K : N;
     if (lda < (a_width > 1 ? a_width : 1)) return GEMM_F64_ERR_LDA;
     if (ldb < (b_width > 1 ? b_width : 1)) return GEMM_F64_ERR_LDB;
@@ -285,6 +289,7 @@ int gemm_ex(const Variant *variants, int count, int transa, int transb, int64_t 
     if (ceil_div(M * N, 256) > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
     hipStream_t stream = (hipStream_t)stream_;
     const int m = (int)M, n = (int)N, k = (int)K;
+    (void)hipGetLastError();   // an error left behind by an earlier, unrelated call must not be reported as this launch's
     hipError_t err = hipSuccess;
     if (!product) {
         if (beta == T(1)) return GEMM_F64_OK;
@@ -323,7 +328,8 @@ int gemm_ex(const Variant *variants, int count, int transa, int transb, int64_t 
 // How one operand with two strides maps onto the row-major kernels.  kRows: the column stride is 1 and the row
 // stride is a leading dimension that covers the row; kColumns: the row stride is 1 and the column stride covers
 // the column (the transposed view of a row-major array); kNeither: anything else (sampled sub-matrices, rows that
-// share elements), which only the element-wise kernel handles.  An extent of 0 or 1 makes its stride irrelevant.
+// share elements), which the tiled kernel handles in its kSampled mode.  An extent of 0 or 1 makes its stride
+// irrelevant.
 enum Layout { kRows, kColumns, kNeither };
 
 inline Layout classify(int64_t rows, int64_t cols, int64_t rs, int64_t cs, int64_t *ld)
@@ -362,7 +368,7 @@ inline int validate_strides(int64_t M, int64_t N, int64_t K, int64_t rsa, int64_
                             int64_t csc)
 {
     if (M < 0 || N < 0 || K < 0) return GEMM_F64_ERR_DIM;
-    if (M > INT32_MAX || N > INT32_MAX || K > INT32_MAX) return GEMM_F64_ERR_TOO_LARGE;
+    if (M > kMaxExtent || N > kMaxExtent || K > kMaxExtent) return GEMM_F64_ERR_TOO_LARGE;
     if (rsa < 1 || csa < 1) return GEMM_F64_ERR_LDA;
     if (rsb < 1 || csb < 1) return GEMM_F64_ERR_LDB;
     if (rsc < 1 || csc < 1) return GEMM_F64_ERR_LDC;
@@ -434,6 +440,7 @@ int gemm_strided(const Variant *variants, int count, int64_t M, int64_t N, int64
                           path.ldc, stream_, -1);
     hipStream_t stream = (hipStream_t)stream_;
     const int m = (int)M, n = (int)N, k = (int)K;
+    (void)hipGetLastError();   // see gemm_ex
     if (!product) {
         if (beta == T(1)) return GEMM_F64_OK;
         return launch_scale<T>(m, n, beta, C, rsc, csc, stream) == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;

@@ -117,13 +117,14 @@ __device__ __forceinline__ void stage_barrier()
 // address is a wave-uniform 64-bit base in SGPRs plus a 32-bit per-lane offset, which costs no
 // vector ALU work when the base advances; and the compiler, which answers every LDS dependency
 // with a full lgkmcnt(0) drain while it knows such a load to be in flight, does not see it.
-// Completion is awaited by the s_waitcnt vmcnt(0) inside stage_barrier().
+// Completion is awaited by the s_waitcnt vmcnt(0) inside stage_barrier().  The statement writes M0 (the
+// LDS destination of the copy) and says so in its clobber list.
 __device__ __forceinline__ void async_copy16(uint32_t voff, const void *sbase, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
                  : "v"(voff), "s"(sbase), "s"(lds_addr)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // The 4-byte form: lane l copies the 4 bytes at sbase + voff(l) to LDS address lds_addr + 4 * l.
@@ -132,7 +133,7 @@ __device__ __forceinline__ void async_copy4(uint32_t voff, const void *sbase, ui
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                  :
                  : "v"(voff), "s"(sbase), "s"(lds_addr)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // The scalar tail of C <- alpha * s + beta * c: t = alpha * s, then t itself when beta is zero (c is

@@ -103,6 +103,66 @@ def fill(out: np.ndarray, seed: int, tag: int, kind: str, row0: int = 0,
     return out
 
 
+def _signed(x: int) -> int:
+    """The 64-bit pattern x as the signed integer torch's int64 holds for it."""
+    x &= MASK64
+    return x - (1 << 64) if x >= (1 << 63) else x
+
+
+def device_matrix(seed: int, tag: int, rows: int, cols: int, ld: int = None, kind: str = "uniform",
+                  dtype=np.float64, device="cuda:0", chunk_rows: int = 2048):
+    """The same matrix as `matrix`, bit for bit (sentinel padding included), generated on `device` with torch
+    integer arithmetic: a (rows, ld) torch tensor.  int64 multiplication and addition wrap modulo 2^64 like the
+    uint64 arithmetic of the NumPy path; logical right shifts are an arithmetic shift followed by a mask."""
+    import torch
+    assert kind in _KINDS
+    ld = max(1, cols) if ld is None else ld
+    assert ld >= max(1, cols)
+    f32 = np.dtype(dtype) == np.float32
+    tdt = torch.float32 if f32 else torch.float64
+    idt = torch.int32 if f32 else torch.int64
+    out = torch.empty((rows, ld), dtype=tdt, device=device)
+    out.view(idt).fill_(PAD_BITS32 if f32 else _signed(PAD_BITS))   # PAD_BITS32 < 2^31 fits an int32 as it is
+    view = out[:, :cols]
+    if kind == "ones":
+        view.fill_(1.0)
+        return out
+    if kind == "zeros":
+        view.fill_(0.0)
+        return out
+
+    def lsr(z, n):
+        return (z >> n) & ((1 << (64 - n)) - 1)
+
+    key = _signed(_stream_key(seed, tag))
+    c = torch.arange(cols, dtype=torch.int64, device=device)[None, :]
+    for r0 in range(0, rows, chunk_rows):
+        n = min(chunk_rows, rows - r0)
+        r = torch.arange(r0, r0 + n, dtype=torch.int64, device=device)[:, None]
+        z = ((r << 32) | c) ^ key
+        z = z + _signed(0x9E3779B97F4A7C15)
+        z = (z ^ lsr(z, 30)) * _signed(0xBF58476D1CE4E5B9)
+        z = (z ^ lsr(z, 27)) * _signed(0x94D049BB133111EB)
+        z = z ^ lsr(z, 31)
+        if kind == "int":
+            v = (lsr(z, 11) % 9).to(torch.float64) - 4.0
+        elif f32:
+            v = lsr(z, 40).to(torch.float64) * (2.0 ** -23) - 1.0
+        else:
+            v = lsr(z, 11).to(torch.float64) * (2.0 ** -52) - 1.0
+        view[r0:r0 + n] = v.to(tdt)
+    return out
+
+
+def device_workload_inputs(w, seed: int = 0, integer: bool = False, dtype=np.float64, device="cuda:0"):
+    """`workload_inputs` generated on the device: three (rows, ld) torch tensors holding the same bits."""
+    kind = "int" if integer else "uniform"
+    ckind = kind if w.c_kind == "uniform" else w.c_kind
+    return (device_matrix(seed, TAG_A, w.M, w.K, w.lda, kind, dtype, device),
+            device_matrix(seed, TAG_B, w.K, w.N, w.ldb, kind, dtype, device),
+            device_matrix(seed, TAG_C, w.M, w.N, w.ldc, ckind, dtype, device))
+
+
 def _bits_view(buf: np.ndarray):
     return (buf.view(np.uint32), np.uint32(PAD_BITS32)) if buf.dtype == np.float32 else (buf.view(np.uint64), np.uint64(PAD_BITS))
 

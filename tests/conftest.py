@@ -10,14 +10,19 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
-    # the tests load the libraries that are built; only if one is missing altogether is it built here
-    # (hipcc cross-compiles for gfx950 without a GPU)
+    # The tests load the libraries that are built.  One that is missing, or that was built from other sources than
+    # the ones on disk (each library carries a digest of its sources), is rebuilt here first; hipcc cross-compiles
+    # for gfx950 without a GPU.  A stale library is never tested: if the rebuild fails, so does the session.
     from paper_2003_00532_amd import build as hip_build
     from oracle import build as oracle_build
-    if not os.path.exists(hip_build.LIB):
-        hip_build.build()
-    if not os.path.exists(oracle_build.LIB):
-        oracle_build.build()
+    for mod, what in ((hip_build, "HIP library"), (oracle_build, "CPU oracle")):
+        if mod.is_stale():
+            try:
+                mod.build()
+            except Exception as e:   # noqa: BLE001
+                raise pytest.UsageError("%s at %s is out of date and could not be rebuilt: %s" % (what, mod.LIB, e))
+            if mod.is_stale():
+                raise pytest.UsageError("%s at %s is still out of date after a rebuild" % (what, mod.LIB))
 
 
 @pytest.fixture(scope="session")

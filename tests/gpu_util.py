@@ -85,3 +85,16 @@ def check_against_oracle(A, B, C0, got, integer, what=""):
     S = np.zeros(want.shape, dtype=np.float64)
     (oracle.gemm_f32_absref if f32 else oracle.gemm_f64_absref)(A, B, S)
     return check_tolerance(got, want, S, what)
+
+
+def check_full_in_row_blocks(A, B, C0, got, integer, what="", block=2048):
+    """Every element of `got` against the oracle, a block of complete rows at a time (row i of the result depends on
+    row i of A and of C alone, so the blocks are independent calls of the same oracle routine; only one block of
+    expected values and scales is alive at a time).  Returns the worst |diff| / S over all elements."""
+    worst = 0.0
+    for r0 in range(0, A.shape[0], block):
+        r1 = min(A.shape[0], r0 + block)
+        ratio = check_against_oracle(A[r0:r1], B, np.ascontiguousarray(C0[r0:r1]), got[r0:r1], integer,
+                                     "%s rows %d..%d" % (what, r0, r1 - 1))
+        worst = max(worst, ratio)
+    return worst

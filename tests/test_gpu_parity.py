@@ -153,6 +153,17 @@ def test_block_split_invariance_on_device(gpu_device):
     pins.pin_block_split_invariance(gpu_util.make_impl(), bitwise_k=False)
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32], ids=["f64", "f32"])
+def test_device_generator_gives_the_host_generator_s_bits(gpu_device, dtype):
+    iv = np.uint32 if dtype == np.float32 else np.uint64
+    w = synth.WORKLOADS["c2_edge"]
+    for integer in (False, True):
+        host = synth.workload_inputs(w, seed=4, integer=integer, dtype=dtype)
+        dev = synth.device_workload_inputs(w, seed=4, integer=integer, dtype=dtype)
+        for h, d in zip(host, dev):
+            assert np.array_equal(h.view(iv), d.cpu().numpy().view(iv))
+
+
 @pytest.mark.parametrize("name", ["c0_256", "c1_2048", "c2_edge"])
 @pytest.mark.parametrize("integer", [True, False], ids=["int", "uniform"])
 def test_full_configs_against_oracle(gpu_device, name, integer):
@@ -177,8 +188,8 @@ def test_edge_config_every_variant(gpu_device, variant):
 @pytest.mark.parametrize("name,nrows", [("c3_8192", 192), ("c4_rankk", 1024)])
 @pytest.mark.parametrize("integer", [True, False], ids=["int", "uniform"])
 def test_large_configs_sampled_rows(gpu_device, name, nrows, integer):
-    # at the full benchmark sizes the oracle computes complete sampled rows (tile-boundary rows plus
-    # hashed random ones); the device result must match on every element of those rows
+    # fast pre-check of the full-result test below: the oracle computes complete sampled rows (tile-boundary rows
+    # plus hashed random ones); the device result must match on every element of those rows
     w = synth.WORKLOADS[name]
     Ab, Bb, Cb = synth.workload_inputs(w, seed=0, integer=integer)
     dA, dB, dC = (gpu_util.to_dev(x) for x in (Ab, Bb, Cb))
@@ -198,6 +209,25 @@ def test_large_configs_sampled_rows(gpu_device, name, nrows, integer):
         S = oracle.abs_rows(A, B, rows)
         ratio = gpu_util.check_tolerance(got, want, S, name + " sampled rows")
         print("%s worst |diff|/S on %d rows = %.3g" % (name, len(rows), ratio))
+
+
+@pytest.mark.parametrize("name", ["c4_rankk", "c3_8192"])
+@pytest.mark.parametrize("integer", [True, False], ids=["int", "uniform"])
+def test_large_configs_full_result(gpu_device, name, integer):
+    # every element of the two largest configurations against the oracle, in the launch configuration the
+    # benchmark times (automatic variant): bit-exact on integer data, within the tolerance on uniform data.
+    # The inputs are generated on the device (the same bits as the host generator, see test_device_generator_*)
+    # and copied to the host for the oracle.
+    w = synth.WORKLOADS[name]
+    dA, dB, dC = synth.device_workload_inputs(w, seed=0, integer=integer)
+    Ab, Bb, Cb = (x.cpu().numpy() for x in (dA, dB, dC))
+    binding.gemm_f64(w.M, w.N, w.K, dA, w.lda, dB, w.ldb, dC, w.ldc)
+    torch.cuda.synchronize()
+    c2 = dC.cpu().numpy()
+    del dA, dB, dC
+    assert synth.padding_intact(c2, w.N)
+    ratio = gpu_util.check_full_in_row_blocks(Ab[:, :w.K], Bb[:, :w.N], Cb[:, :w.N], c2[:, :w.N], integer, name)
+    print("%s %s full result: worst |diff|/S = %.3g" % (name, "int" if integer else "uniform", ratio))
 
 
 @pytest.mark.parametrize("name", ["c3_8192", "c4_rankk"])

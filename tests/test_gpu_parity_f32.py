@@ -139,6 +139,25 @@ def test_large_configs_sampled_rows(gpu_device, name, nrows, integer):
         print("f32 %s worst |diff|/S on %d rows = %.3g (u = %.3g)" % (name, len(rows), ratio, 2.0 ** -24))
 
 
+@pytest.mark.parametrize("name", ["c4_rankk", "c3_8192"])
+@pytest.mark.parametrize("integer", [True, False], ids=["int", "uniform"])
+def test_large_configs_full_result(gpu_device, name, integer):
+    # every element of the two largest configurations against the oracle, in the launch configuration the
+    # benchmark times (automatic variant): bit-exact on integer data, within the tolerance on uniform data.
+    # The inputs are generated on the device (the same bits as the host generator, see test_device_generator_*)
+    # and copied to the host for the oracle.
+    w = synth.WORKLOADS[name]
+    dA, dB, dC = synth.device_workload_inputs(w, seed=0, integer=integer, dtype=F32)
+    Ab, Bb, Cb = (x.cpu().numpy() for x in (dA, dB, dC))
+    binding.gemm_f32(w.M, w.N, w.K, dA, w.lda, dB, w.ldb, dC, w.ldc)
+    torch.cuda.synchronize()
+    c2 = dC.cpu().numpy()
+    del dA, dB, dC
+    assert synth.padding_intact(c2, w.N)
+    ratio = gpu_util.check_full_in_row_blocks(Ab[:, :w.K], Bb[:, :w.N], Cb[:, :w.N], c2[:, :w.N], integer, "f32 " + name)
+    print("f32 %s %s full result: worst |diff|/S = %.3g (u = %.3g)" % (name, "int" if integer else "uniform", ratio, 2.0 ** -24))
+
+
 @pytest.mark.parametrize("name", ["c3_8192", "c4_rankk"])
 def test_large_configs_all_ones_everywhere(gpu_device, name):
     w = synth.WORKLOADS[name]

@@ -57,6 +57,16 @@ def test_argument_validation_happens_before_any_launch():
     assert raw(2, 2, 2, p + 4, 2, p, 2, p, 2) == -6
     assert raw(2, 2, 2, p, 2, p, 2, p + 2, 2) == -6
     assert raw(2 ** 31, 2, 2, p, 2, p, 2, p, 2) == -8
+    # the kernels form "tile origin + tile size" in 32-bit integers: extents within one tile of 2^31 - 1 are
+    # refused (in every position, transposed or not) rather than allowed to wrap; the bound itself passes validation
+    big, ok = 2 ** 31 - 128, 2 ** 31 - 129
+    assert raw(big, 1, 1, p, 1, p, 1, p, 1) == -8
+    assert raw(1, big, 1, p, 1, p, big, p, big) == -8
+    assert raw(1, 1, big, p, big, p, 1, p, 1) == -8
+    gen = binding.load().gemm_f64_general_ex
+    assert gen(1, 0, big, 1, 1, 1.0, p, big, p, 1, 1.0, p, 1, None, 1) == -8
+    assert gen(1, 0, ok, 1, 1, 1.0, p, ok - 1, p, 1, 1.0, p, 1, None, 1) == -2   # passes the size check, fails the next
+    assert binding.load().gemm_f64_strided(big, 1, 1, 1.0, p, 1, 1, p, 1, 1, 1.0, p, 1, 1, None) == -8
     assert raw(2, 2, 2, p, 2, p, 2, p, 2, variant=99) == -9
     # empty problems succeed without touching anything, even with null pointers
     assert raw(0, 5, 5, None, 5, None, 5, None, 5) == 0
