@@ -34,7 +34,9 @@ enum {
     GEMM_F64_ERR_ALIGN = -6,     /* a pointer is not 8-byte aligned                      */
     GEMM_F64_ERR_LAUNCH = -7,    /* the HIP runtime refused the launch (see hipGetLastError) */
     GEMM_F64_ERR_TOO_LARGE = -8, /* M, N or K above 2^31 - 129 (32-bit tile arithmetic)     */
-    GEMM_F64_ERR_VARIANT = -9    /* unknown kernel variant index                         */
+    GEMM_F64_ERR_VARIANT = -9,   /* unknown kernel variant index                         */
+    GEMM_F64_ERR_SCRATCH = -10   /* gemm_f64_general_static: the split this problem wants needs more than the
+                                    library's fixed scratch buffer, or that buffer could not be located */
 };
 
 /*
@@ -214,6 +216,33 @@ int gemm_f64_general_ws(int transa, int transb, int64_t M, int64_t N, int64_t K,
                         const double *B, int64_t ldb,
                         double beta, double *C, int64_t ldc,
                         void *workspace, int64_t workspace_bytes, void *stream);
+
+/*
+ * gemm_f64_general_static: gemm_f64_general_ws for callers that can neither allocate device memory nor hold a
+ * workspace of their own: code under HIP graph capture, tight serving loops, harnesses that forbid allocation.
+ * The workspace is a fixed buffer of GEMM_F64_STATIC_SCRATCH_BYTES inside the library's device image (one copy per
+ * GPU, held from the moment the library is loaded on that GPU until the process ends).  The call allocates nothing
+ * and frees nothing; it launches the same kernels as gemm_f64_general_ws.
+ *
+ * Which plan runs: the one gemm_f64_general_ws would run with a workspace of exactly
+ * gemm_f64_split_k_workspace_bytes(transa, transb, M, N, K, compute units) bytes, i.e. the plan the rule prefers
+ * when memory is no object; the results of the two calls are identical bit for bit.  If that plan needs more than
+ * GEMM_F64_STATIC_SCRATCH_BYTES the call returns GEMM_F64_ERR_SCRATCH and launches nothing (use
+ * gemm_f64_general_ws with a workspace of your own, or gemm_f64_general).  A problem the rule would not split
+ * does not touch the buffer.  GEMM_F64_ERR_SCRATCH is also returned if the runtime cannot give the address of the
+ * buffer on the current device (looked up once per device, on the first call there).
+ *
+ * The buffer keeps whatever the last call left in it; nothing in it needs to start from zero, because the first
+ * launch of a split overwrites every element of every slab that the second launch reads.  Every call on a GPU
+ * shares that GPU's buffer: calls that may overlap in time on one GPU (different streams without an ordering
+ * between them, or host threads launching at once) race on it and must be ordered by the caller.
+ * All other arguments, folding rules, error codes and the tolerance are those of gemm_f64_general_ws.
+ */
+#define GEMM_F64_STATIC_SCRATCH_BYTES (64ll << 20)
+int gemm_f64_general_static(int transa, int transb, int64_t M, int64_t N, int64_t K,
+                            double alpha, const double *A, int64_t lda,
+                            const double *B, int64_t ldb,
+                            double beta, double *C, int64_t ldc, void *stream);
 
 /*
  * gemm_f64_split_k_plan: the pure host-side rule behind gemm_f64_general_ws (no device is touched).  Writes the

@@ -97,6 +97,8 @@ def load():
     lp = ctypes.POINTER(i64)
     lib.gemm_f64_strided_path.argtypes = [i64] * 9 + [ip, ip, ip, lp, lp, lp, lp, lp, lp]
     lib.gemm_f64_strided_path.restype = ci
+    lib.gemm_f64_general_static.argtypes = [ci, ci, i64, i64, i64, cd, vp, i64, vp, i64, cd, vp, i64, vp]
+    lib.gemm_f64_general_static.restype = ci
     lib.gemm_f64_strided.argtypes = [i64, i64, i64, cd, vp, i64, i64, vp, i64, i64, cd, vp, i64, i64, vp]
     lib.gemm_f64_strided.restype = ci
     lib.gemm_f32_strided.argtypes = [i64, i64, i64, cf, vp, i64, i64, vp, i64, i64, cf, vp, i64, i64, vp]
@@ -262,6 +264,15 @@ def gemm_f64_general_ws(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C,
     """gemm_f64_general with a device workspace on offer (the library may split the k range)."""
     _check(load().gemm_f64_general_ws(int(transa), int(transb), M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
                                       _ptr(C), ldc, _ptr(workspace), int(workspace_bytes), _stream(stream)))
+
+
+def gemm_f64_general_static(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream=None):
+    """gemm_f64_general_ws on the library's own fixed scratch buffer: allocates nothing."""
+    _check(load().gemm_f64_general_static(int(transa), int(transb), M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                          _ptr(C), ldc, _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = 64 << 20   # GEMM_F64_STATIC_SCRATCH_BYTES
 
 
 def gemm_f32_general_ws(transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace, workspace_bytes, stream=None):

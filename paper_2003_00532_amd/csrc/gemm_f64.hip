@@ -1,6 +1,8 @@
 // libgemm_f64.so, double-precision entry points (declared and documented in include/gemm_f64.h).
 #include "gemm_host.hpp"
 
+#include <mutex>
+
 using namespace gemm_detail;
 
 namespace {
@@ -59,6 +61,9 @@ extern "C" const char *gemm_f64_strerror(int code)
     case GEMM_F64_ERR_LAUNCH: return "HIP kernel launch failed";
     case GEMM_F64_ERR_TOO_LARGE: return "dimension exceeds 2^31 - 129";
     case GEMM_F64_ERR_VARIANT: return "unknown kernel variant";
+    case GEMM_F64_ERR_SCRATCH:
+        return "the split this problem wants needs more than the library's fixed scratch buffer (or the buffer could not be "
+               "located on this device); use gemm_f64_general_ws with a workspace of your own";
     default: return "unknown error code";
     }
 }
@@ -113,6 +118,57 @@ extern "C" int gemm_f64_general_ws(int transa, int transb, int64_t M, int64_t N,
 {
     return gemm_ex<double>(kVariants, kNumVariants, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, -1,
                        workspace, workspace_bytes);
+}
+
+// ---- the entry point that allocates nothing ---------------------------------------------------------------------
+// Scratch for the slabs of a split k range, part of the device image: every GPU the library is loaded on holds its
+// own copy at its own address.  In host code the name below is only a handle for hipGetSymbolAddress; the address
+// that kernels and copies are given is the one that call returns, looked up once per device.
+static __device__ __align__(256) unsigned char scratch[GEMM_F64_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};   // per device, filled on the first call with that device current
+
+// Device address of `scratch` on the current device; nullptr when it cannot be had.
+void *scratch_on_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" int gemm_f64_general_static(int transa, int transb, int64_t M, int64_t N, int64_t K, double alpha, const double *A,
+                                       int64_t lda, const double *B, int64_t ldb, double beta, double *C, int64_t ldc,
+                                       void *stream)
+{
+    // argument errors first, exactly as the workspace form reports them (nothing is launched for any of them)
+    const bool product = (alpha != 0.0) && K != 0;
+    const int rc = validate(transa, transb, M, N, K, product, A, lda, B, ldb, C, ldc);
+    if (rc != GEMM_F64_OK) return rc;
+    if (M == 0 || N == 0 || !product)
+        return gemm_ex<double>(kVariants, kNumVariants, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, -1);
+    // what the rule would like to have when memory is no object
+    const Plan plan = plan_split_k(kVariants, kNumVariants, transa, transb, M, N, K, current_cu_count(), (int)sizeof(double), INT64_MAX);
+    if (plan.splits <= 1)
+        return gemm_ex<double>(kVariants, kNumVariants, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, -1);
+    const int64_t wanted = (int64_t)plan.splits * M * N * (int64_t)sizeof(double);
+    if (wanted > GEMM_F64_STATIC_SCRATCH_BYTES) return GEMM_F64_ERR_SCRATCH;
+    void *ptr = scratch_on_current_device();
+    if (ptr == nullptr) return GEMM_F64_ERR_SCRATCH;
+    return gemm_ex<double>(kVariants, kNumVariants, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, -1, ptr,
+                           wanted);
 }
 
 extern "C" int gemm_f64_strided(int64_t M, int64_t N, int64_t K, double alpha, const double *A, int64_t rsa, int64_t csa,

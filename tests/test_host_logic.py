@@ -72,7 +72,7 @@ def test_argument_validation_happens_before_any_launch():
     assert raw(0, 5, 5, None, 5, None, 5, None, 5) == 0
     assert raw(5, 0, 5, None, 5, None, 1, None, 1) == 0
     assert raw(5, 5, 0, None, 1, None, 5, p, 5) == 0
-    for code in range(-9, 1):
+    for code in range(-10, 1):
         assert "unknown error" not in binding.gemm_f64_strerror(code)
     assert "unknown" in binding.gemm_f64_strerror(-1234)
     with pytest.raises(binding.GemmF64Error):
