@@ -248,6 +248,16 @@ def main():
     kernel_ms = sum(per_launch_ms) / len(per_launch_ms)
     kernel_ms_median = sorted(per_launch_ms)[len(per_launch_ms) // 2]
 
+    # the same number of launches back to back, one event on either side (how a caller would stream them): for short
+    # kernels the event records between launches above cost a few per cent
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    back_to_back_ms = e0.elapsed_time(e1) / args.steps
+
     ms_per_step = wall * 1e3 / args.steps
     gflops = w.flops / (ms_per_step * 1e-3) / 1e9
     achieved_tflops = w.flops / (kernel_ms * 1e-3) / 1e12
@@ -270,13 +280,15 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: %s row-major C += A*B, M=%d N=%d K=%d, lda=%d ldb=%d ldc=%d, A,B uniform[-1,1) seed %d, C %s"
                                % (w.name, prec, w.M, w.N, w.K, w.lda, w.ldb, w.ldc, args.seed, w.c_kind),
-                   "kernel_variant": vname, "device": props.name, "compute_units": props.multi_processor_count},
+                   "kernel_variant": vname, "device": props.name, "compute_units": props.multi_processor_count,
+                   "library_build_id": binding.gemm_f64_build_id()},
         "pct_of_%s_mfma_peak" % prec: round(100.0 * gflops / (peak * 1e3), 2),
         "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved_tflops / peak, 4),
                      "traffic": traffic, "traffic_source": traffic_source, "kernel_ms": round(kernel_ms, 4),
                      "kernel_ms_min": round(min(per_launch_ms), 4), "kernel_ms_median": round(kernel_ms_median, 4),
-                     "kernel_ms_max": round(max(per_launch_ms), 4),
+                     "kernel_ms_max": round(max(per_launch_ms), 4), "back_to_back_ms": round(back_to_back_ms, 4),
+                     "back_to_back_frac": round(w.flops / (back_to_back_ms * 1e-3) / 1e12 / peak, 4),
                      "algorithmic_flops_per_launch": w.flops, "algorithmic_bytes_per_launch": alg_bytes},
     }
     # The peak recomputed from what the device reports (compute units x 4 SIMDs x flops per MFMA / issue cycles x clock)
