@@ -154,8 +154,13 @@ def other_workloads(gemm_ex, choose, variant_name, np_dtype, peak, seed, stream,
         def call():
             gemm_ex(w.M, w.N, w.K, dA, w.lda, dB, w.ldb, dC, w.ldc, stream=stream, variant=-1)
 
-        for _ in range(3):
-            call()
+        # warm-up by time, not by count: after an idle stretch the chip takes tens of milliseconds of load to reach
+        # its clock (the first launches of a 0.25 ms kernel run up to 25 % slower)
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < 0.5:
+            for _ in range(10):
+                call()
+            torch.cuda.synchronize()
         sep, b2b = time_launches(call, stream, launches)
         ms = sum(sep) / len(sep)
         out[name] = {"kernel_variant": variant_name(choose(w.M, w.N, w.K, cus)), "launches": launches,
@@ -232,6 +237,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # short kernels: keep warming until the chip has been under load for half a second (clock ramp), see other_workloads
+    t0 = time.perf_counter()
+    while w.flops < 1e11 and time.perf_counter() - t0 < 0.5:
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
 
     # whole-job wall time over exactly `steps` steps, and per-launch durations from HIP events recorded
     # on the launch stream (event i sits between launch i-1 and launch i)

@@ -315,6 +315,19 @@ int gemm_f64_mfma_probe(int64_t iterations, double *sink, int64_t sink_elems, vo
  */
 int gemm_f64_device_peak(int *compute_units, int *clock_khz, double *fp64_mfma_tflops, double *fp32_mfma_tflops);
 
+/*
+ * gemm_f64_set_epilogue_mode: a diagnostic switch for tests and measurements, process-wide, not meant for production
+ * code (every other entry point is a pure function of its arguments).  With alpha == beta == 1 (the operation of the
+ * paper's Section 2.1) the double-precision kernels update C in one of two ways that give the same bits: each lane
+ * loads, adds and stores its elements, or it sends its sums to the memory system as floating-point additions without
+ * return value (each element of C belongs to exactly one lane, so this is the same single rounding, and the order of
+ * the additions is irrelevant).  The second form frees a workgroup's registers one memory latency earlier and is what
+ * the library picks when K >= 256, C has at least 2^20 elements and C is ordinary device memory.
+ *   mode 0  automatic (the default);  1  always load, add, store;  2  additions in memory whenever C is device memory.
+ * Returns the previous mode, or GEMM_F64_ERR_DIM for any other value.
+ */
+int gemm_f64_set_epilogue_mode(int mode);
+
 /* Static description of a return code; never NULL, never freed. */
 const char *gemm_f64_strerror(int code);
 

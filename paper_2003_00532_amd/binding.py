@@ -54,6 +54,8 @@ def load():
     lib.gemm_f64_strerror.restype = ctypes.c_char_p
     lib.gemm_f64_version.argtypes = []
     lib.gemm_f64_version.restype = ci
+    lib.gemm_f64_set_epilogue_mode.argtypes = [ci]
+    lib.gemm_f64_set_epilogue_mode.restype = ci
     lib.gemm_f64_build_id.argtypes = []
     lib.gemm_f64_build_id.restype = ctypes.c_char_p
     lib.gemm_f32.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
@@ -177,6 +179,13 @@ def gemm_f64_tile_of_block(block, tiles_m, tiles_n):
 
 def gemm_f64_version() -> int:
     return int(load().gemm_f64_version())
+
+
+def gemm_f64_set_epilogue_mode(mode: int) -> int:
+    """Diagnostic switch: 0 automatic, 1 load-add-store, 2 additions in memory; returns the previous mode."""
+    rc = int(load().gemm_f64_set_epilogue_mode(int(mode)))
+    _check(rc if rc < 0 else 0)
+    return rc
 
 
 def gemm_f64_build_id() -> str:

@@ -42,7 +42,7 @@ extern "C" int gemm_f64_tile_of_block(int64_t block, int64_t tiles_m, int64_t ti
         block < 0 || block >= tiles_m * tiles_n || !tile_m || !tile_n)
         return GEMM_F64_ERR_DIM;
     uint32_t tm = 0, tn = 0;
-    tile_of_block((uint32_t)block, (uint32_t)tiles_m, (uint32_t)tiles_n, tm, tn);
+    tile_of_block((uint32_t)block, make_tile_map((uint32_t)tiles_m, (uint32_t)tiles_n), tm, tn);
     *tile_m = tm;
     *tile_n = tn;
     return GEMM_F64_OK;
@@ -216,3 +216,19 @@ extern "C" int64_t gemm_f64_split_k_workspace_bytes(int transa, int transb, int6
     if (gemm_f64_split_k_plan(transa, transb, M, N, K, num_cu, INT64_MAX, nullptr, &splits, nullptr) != GEMM_F64_OK) return 0;
     return splits > 1 ? (int64_t)splits * M * N * (int64_t)sizeof(double) : 0;
 }
+
+extern "C" int gemm_f64_set_epilogue_mode(int mode)
+{
+    if (mode != kEpilogueAuto && mode != kEpilogueLoadStore && mode != kEpilogueInMemory) return GEMM_F64_ERR_DIM;
+    return g_epilogue_mode.exchange(mode);
+}
+
+#ifdef GEMM_PHASE_TRACE
+// Diagnostic builds only: install (or remove, with NULL) the device buffer the kernels of this file trace into;
+// it must hold 8 * (number of workgroups of the launch) 64-bit slots.
+extern "C" int gemm_debug_set_trace(void *device_buffer)
+{
+    unsigned long long *p = static_cast<unsigned long long *>(device_buffer);
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_phase_trace), &p, sizeof(p)) == hipSuccess ? 0 : -1;
+}
+#endif

@@ -6,6 +6,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "gemm_mfma.hpp"
 
 namespace gemm_detail {
@@ -191,29 +193,31 @@ hipError_t launch_mfma_t(const Job<T> &j)
 {
     constexpr int BK = 8 * (16 / (int)sizeof(T));
     const int tiles_m = (int)ceil_div(j.M, BM), tiles_n = (int)ceil_div(j.N, BN);
-    const dim3 grid((unsigned)((int64_t)tiles_m * tiles_n), (unsigned)j.slices), block(kThreads);
+    const int64_t tiles = (int64_t)tiles_m * tiles_n;
+    const bool vec = async_copies_possible<T>(j.lda, j.ldb);
+    // The lean kernel assumes full tiles everywhere and whole K stages (in every slice).
+    const bool lean = !j.sampled && vec && (j.M % BM == 0) && (j.N % BN == 0) && (j.K % BK == 0) && (j.split.k_chunk % BK == 0);
+    const dim3 grid((unsigned)tiles, (unsigned)j.slices), block(kThreads);
+    const TileMap map = make_tile_map((uint32_t)tiles_m, (uint32_t)tiles_n);
     if (j.sampled) {
         // built for one tile shape only (the mode needs more registers than the largest tile leaves)
         if constexpr (BM == 64 && BN == 64) {
             hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kSampled, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
-                               j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, tiles_m, tiles_n, j.split, j.es);
+                               j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, map, j.split, j.es);
             return hipGetLastError();
         } else {
             return hipErrorInvalidValue;
         }
     }
-    const bool vec = async_copies_possible<T>(j.lda, j.ldb);
-    // The lean kernel assumes full tiles everywhere and whole K stages (in every slice).
-    const bool lean = vec && (j.M % BM == 0) && (j.N % BN == 0) && (j.K % BK == 0) && (j.split.k_chunk % BK == 0);
     if (lean)
         hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kLean, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
-                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, tiles_m, tiles_n, j.split, j.es);
+                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, map, j.split, j.es);
     else if (vec)
         hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kGeneric, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
-                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, tiles_m, tiles_n, j.split, j.es);
+                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, map, j.split, j.es);
     else
         hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kStaged, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
-                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, tiles_m, tiles_n, j.split, j.es);
+                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, map, j.split, j.es);
     return hipGetLastError();
 }
 
@@ -261,6 +265,35 @@ hipError_t launch_scale(int M, int N, T beta, T *C, int64_t rsc, int64_t csc, hi
     return hipGetLastError();
 }
 
+// How C is updated when alpha == beta == 1 (the paper's own operation).  Either each lane loads its elements, adds
+// and stores; or it hands its sums to the memory system as floating-point additions performed at the L2 cache
+// (global_atomic_add_f64 without return).  Every element of C belongs to exactly one lane, so the second form is the
+// same single rounding of c + s and the result is the same bits (tested on the device against the first form, special
+// values included); what differs is that the wave does not wait for C to arrive, so its registers and LDS are free for
+// the next workgroup one memory latency earlier.  Measured at 16384^2 x K: K = 256 2.32 -> 2.22 ms, K = 512 4.24 ->
+// 4.12 ms, K = 1024 8.06 -> 7.96 ms; but K = 128 1.42 -> 1.77 ms, because the additions themselves take 1.64 ms for
+// 16384^2 elements (load and store: 0.88 ms) and must fit under the MFMA time, which they do from K = 242 upwards.
+// Hardware floating-point additions in memory are only defined for ordinary device memory (not for host memory
+// mapped into the device, nor managed memory), so the owner of C is asked first; single precision keeps the first
+// form (its additions in memory do not honour denormals).
+enum { kEpilogueAuto = 0, kEpilogueLoadStore = 1, kEpilogueInMemory = 2 };
+inline std::atomic<int> g_epilogue_mode{kEpilogueAuto};   // a diagnostic switch, see gemm_f64_set_epilogue_mode
+
+template <typename T>
+bool accumulate_in_memory(int64_t M, int64_t N, int64_t K, T alpha, T beta, const T *C)
+{
+    if (!std::is_same<T, double>::value || alpha != T(1) || beta != T(1)) return false;
+    const int mode = g_epilogue_mode.load(std::memory_order_relaxed);
+    if (mode == kEpilogueLoadStore) return false;
+    if (mode == kEpilogueAuto && (K < 256 || M * N < ((int64_t)1 << 20))) return false;
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, C) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return attr.type == hipMemoryTypeDevice;
+}
+
 inline int current_cu_count()
 {
     int dev = 0, v = 0;
@@ -297,6 +330,7 @@ int gemm_ex(const Variant *variants, int count, int transa, int transb, int64_t 
         return err == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
     }
     Job<T> job{transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream, 1, SplitK{k, 0, 0, 0}};
+    job.split.flags = accumulate_in_memory<T>(M, N, K, alpha, beta, C) ? kFlagAtomicC : 0;
     if (variant == -1) {
         const Plan plan = plan_split_k(variants, count, transa, transb, M, N, K, current_cu_count(), (int)sizeof(T),
                                        workspace ? workspace_bytes : 0);

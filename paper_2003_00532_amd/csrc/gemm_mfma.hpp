@@ -70,7 +70,9 @@ template <> struct Elem<float> {
 struct SplitK {
     int k_chunk;
     int64_t step_a, step_b, step_c;
+    int flags = 0;   // kFlag* bits
 };
+constexpr int kFlagAtomicC = 1;   // alpha = beta = 1: add the sums to C in memory instead of load, add, store
 
 // Elements between neighbours along the contiguous index of op(A) and op(B) and along the rows of C; read by the
 // kSampled mode only (1 everywhere else).
@@ -78,26 +80,106 @@ struct ElemStrides {
     int64_t a, b, c;
 };
 
+// Optional phase trace (diagnostic builds only, -DGEMM_PHASE_TRACE): thread 0 of every workgroup stores the constant
+// 100 MHz clock at a few points of its life, and where it ran, into 8 slots of a buffer the host has installed.
+#ifdef GEMM_PHASE_TRACE
+static __device__ unsigned long long *g_phase_trace;
+#define GEMM_PHASE_MARK(i)                                                                                      \
+    do {                                                                                                        \
+        if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) == 0 && g_phase_trace)                             \
+            g_phase_trace[((size_t)blockIdx.x + (size_t)gridDim.x * blockIdx.y) * 8 + (i)] = __builtin_amdgcn_s_memrealtime(); \
+    } while (0)
+#define GEMM_PHASE_CLOCK(i)                                                                                     \
+    do {                                                                                                        \
+        if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) == 0 && g_phase_trace)                             \
+            g_phase_trace[((size_t)blockIdx.x + (size_t)gridDim.x * blockIdx.y) * 8 + (i)] = __builtin_amdgcn_s_memtime(); \
+    } while (0)
+#define GEMM_PHASE_WHERE()                                                                                      \
+    do {                                                                                                        \
+        if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) == 0 && g_phase_trace)                             \
+            g_phase_trace[((size_t)blockIdx.x + (size_t)gridDim.x * blockIdx.y) * 8 + 7] =                      \
+                (unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 4) |                                 \
+                ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32);                         \
+    } while (0)
+#else
+#define GEMM_PHASE_MARK(i) do { } while (0)
+#define GEMM_PHASE_CLOCK(i) do { } while (0)
+#define GEMM_PHASE_WHERE() do { } while (0)
+#endif
+
+// Division of a non-negative 32-bit number by a divisor fixed on the host, as a multiplication and a shift: the
+// quotient is exact for every n < 2^31.  With L = ceil(log2 d) and m = floor(2^(31+L) / d) + 1 (which fits in 32 bits
+// because d > 2^(L-1)), n * m / 2^(31+L) exceeds n / d by less than n / 2^(31+L) < 2^-L <= 1/d, so the floor is the
+// same.  On the device every operand is wave-uniform and the whole computation stays on the scalar unit: a division
+// by a run-time value would instead go through the vector unit's reciprocal, where, in a workgroup that starts while
+// older ones are in their K loops, each instruction queues behind the matrix instructions of those waves.
+struct FastDiv {
+    uint32_t d, magic, shift;
+};
+
+inline FastDiv make_fast_div(uint32_t d)
+{
+    if (d <= 1) return FastDiv{1, 0, 0};
+    uint32_t L = 0;
+    while (((uint64_t)1 << L) < d) ++L;   // ceil(log2 d) >= 1
+    return FastDiv{d, (uint32_t)((((uint64_t)1 << (31 + L)) / d) + 1), L - 1};
+}
+
+__host__ __device__ inline uint32_t fast_div(uint32_t n, const FastDiv &f)
+{
+#ifdef __HIP_DEVICE_COMPILE__
+    const uint32_t hi = __umulhi(n, f.magic);
+#else
+    const uint32_t hi = (uint32_t)(((uint64_t)n * f.magic) >> 32);
+#endif
+    return f.d == 1 ? n : (hi >> f.shift);
+}
+
 // Workgroup id -> tile coordinates.  Block b runs on XCD b % kXcds.  Each XCD receives a
 // contiguous run of the "grouped" tile order (kGroupM tile rows at a time, column by column
 // inside a group), so the workgroups resident on one XCD at any moment form a compact patch of C
 // and re-use each other's A and B panels in that XCD's L2.
 // All quantities fit in 32 bits: the host refuses problems with more than 2^31 - 1 blocks of 256 outputs.
-__host__ __device__ inline void tile_of_block(uint32_t b, uint32_t tiles_m, uint32_t tiles_n, uint32_t &tm,
-                                              uint32_t &tn)
+// The host prepares what does not depend on the block (TileMap); the two divisions by run-time values (by the
+// tiles of a group, and by the height of the last, shorter group) are FastDiv multiplications.
+struct TileMap {
+    uint32_t tiles_m, tiles_n;
+    uint32_t per, rem;     // tiles per XCD and how many XCDs get one more
+    FastDiv width;         // tiles in a full group of kGroupM tile rows
+    FastDiv last;          // height of the last group (tiles_m % kGroupM, or kGroupM)
+};
+
+inline TileMap make_tile_map(uint32_t tiles_m, uint32_t tiles_n)
 {
     const uint32_t total = tiles_m * tiles_n;
-    const uint32_t per = total / kXcds, rem = total % kXcds;
-    const uint32_t x = b % kXcds, s = b / kXcds;
-    const uint32_t start = x * per + (x < rem ? x : rem);
-    const uint32_t logical = start + s;
-    const uint32_t width = kGroupM * tiles_n;
-    const uint32_t g = logical / width;
+    const uint32_t last = tiles_m % kGroupM ? tiles_m % kGroupM : kGroupM;
+    return TileMap{tiles_m, tiles_n, total / kXcds, total % kXcds, make_fast_div(kGroupM * tiles_n), make_fast_div(last)};
+}
+
+// Position, in the grouped order, of the tile of workgroup b.
+__host__ __device__ inline uint32_t position_of_block(uint32_t b, const TileMap &map)
+{
+    static_assert(kXcds == 8 && kGroupM == 8, "the shifts below");
+    const uint32_t x = b & 7, s = b >> 3;
+    const uint32_t start = x * map.per + (x < map.rem ? x : map.rem);
+    return start + s;
+}
+
+// Tile coordinates of position `logical` of the grouped order.
+__host__ __device__ inline void tile_at(uint32_t logical, const TileMap &map, uint32_t &tm, uint32_t &tn)
+{
+    const uint32_t g = fast_div(logical, map.width);
     const uint32_t first_m = g * kGroupM;
-    const uint32_t gsz = (tiles_m - first_m) < (uint32_t)kGroupM ? (tiles_m - first_m) : (uint32_t)kGroupM;
-    const uint32_t in_g = logical - g * width;
-    tn = in_g / gsz;
+    const bool full = map.tiles_m - first_m >= (uint32_t)kGroupM;
+    const uint32_t gsz = full ? (uint32_t)kGroupM : map.tiles_m - first_m;
+    const uint32_t in_g = logical - g * map.width.d;
+    tn = full ? (in_g >> 3) : fast_div(in_g, map.last);
     tm = first_m + (in_g - tn * gsz);
+}
+
+__host__ __device__ inline void tile_of_block(uint32_t b, const TileMap &map, uint32_t &tm, uint32_t &tn)
+{
+    tile_at(position_of_block(b, map), map, tm, tn);
 }
 
 // Workgroup barrier that also publishes this wave's LDS traffic: every LDS read, LDS write and
@@ -374,8 +456,11 @@ struct Panel {
 template <typename T, int BM, int BN, int WM, int WN, int MODE, bool TA, bool TB>
 __global__ void __launch_bounds__(kThreads, 2)
 gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, int64_t lda, const T *__restrict__ B_,
-                 int64_t ldb, T beta, T *__restrict__ C_, int64_t ldc, int tiles_m, int tiles_n, SplitK split, ElemStrides es)
+                 int64_t ldb, T beta, T *__restrict__ C_, int64_t ldc, TileMap map, SplitK split, ElemStrides es)
 {
+    GEMM_PHASE_MARK(0);
+    GEMM_PHASE_CLOCK(1);
+    GEMM_PHASE_WHERE();
     // this workgroup's slice of k (all of it when the grid has height 1)
     const int slice = blockIdx.y;
     const int K = min(split.k_chunk, K_total - slice * split.k_chunk);
@@ -412,7 +497,7 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, i
     const int lg = l >> 4, li = l & 15;
 
     uint32_t tm_u, tn_u;
-    tile_of_block(blockIdx.x, (uint32_t)tiles_m, (uint32_t)tiles_n, tm_u, tn_u);
+    tile_of_block(blockIdx.x, map, tm_u, tn_u);
     const int m0 = (int)tm_u * BM, n0 = (int)tn_u * BN;
 
     const bool tile_full = (m0 + BM <= M) && (n0 + BN <= N);
@@ -489,6 +574,7 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, i
         }
     }
     stage_barrier();
+    GEMM_PHASE_MARK(3);
     read_frags(0, 0, fa0, fb0);
 
     // Stage s lives in buffer s % 2.  Per iteration: the second half's fragments are read while the
@@ -536,13 +622,6 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, i
         __builtin_amdgcn_sched_barrier(0);
         mfma_range(fa1, fb1, 0, HALF);
     };
-    int s = 0;
-    for (; s + 1 < nk; s += 2) {
-        iteration(s, std::integral_constant<int, 0>{});
-        iteration(s + 1, std::integral_constant<int, 1>{});
-    }
-    if (s < nk) iteration(s, std::integral_constant<int, 0>{});
-
     // C <- alpha * (A B) + beta * C, C read (unless beta is zero: then it may hold anything, NaN
     // included) and written exactly once per element, after the K loop.  With alpha = beta = 1 the
     // update is the single rounding of acc + c (see scaled_update).  Loads are issued in batches
@@ -552,66 +631,100 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, i
     // between the four result registers of an accumulator tile and 16 * ldc between tile rows, added up
     // as the loops go (a 64-bit add per row instead of a multiply per element); columns of one row are
     // a compile-time offset apart.
-    const int row_base = m0 + wm * TM + EL::d_row(0, lg);
-    const int col_base = n0 + wn * TN + li;
-    constexpr int ROW_STEP = EL::d_row(1, 0) - EL::d_row(0, 0);   // 4 for double, 1 for float
-    static_assert(EL::d_row(2, 0) - EL::d_row(1, 0) == ROW_STEP && EL::d_row(3, 0) - EL::d_row(2, 0) == ROW_STEP, "");
-    constexpr int MB = (MI >= 2) ? 2 : 1;
-    const int64_t cs_c = SAMPLED ? es.c : 1;   // elements between neighbouring columns of C
-    T *const c_lane = C + (int64_t)row_base * ldc + col_base * cs_c;
-    const int64_t r_step = (int64_t)ROW_STEP * ldc, mi_step = 16 * ldc;
-    // Three forms, chosen once per workgroup: alpha = beta = 1 (the paper's own operation: one addition
-    // per element), beta = 0 (C is not read) and the general one.
-    constexpr int kUnit = 0, kOverwrite = 1, kScaled = 2;
-    auto epilogue = [&](auto kind_tag) {
-        constexpr int KIND = decltype(kind_tag)::value;
-        constexpr bool UNIT = KIND == kUnit;
-        constexpr bool read_c = KIND != kOverwrite;
-        T *c_mb = c_lane;
-#pragma unroll
-        for (int mb = 0; mb < MI; mb += MB) {
-            T cin[MB][NI][4];
-            T *c_mi = c_mb;
-#pragma unroll
-            for (int mi = mb; mi < mb + MB; ++mi) {
-                T *c_r = c_mi;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = row_base + mi * 16 + r * ROW_STEP;
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni) {
-                        const int col = col_base + ni * 16;
-                        if (read_c && (!GENERIC || tile_full || (row < M && col < N))) cin[mi - mb][ni][r] = c_r[ni * 16 * cs_c];
-                        else cin[mi - mb][ni][r] = T(0);
+    auto write_tile = [&]() {
+        const int row_base = m0 + wm * TM + EL::d_row(0, lg);
+        const int col_base = n0 + wn * TN + li;
+        constexpr int ROW_STEP = EL::d_row(1, 0) - EL::d_row(0, 0);   // 4 for double, 1 for float
+        static_assert(EL::d_row(2, 0) - EL::d_row(1, 0) == ROW_STEP && EL::d_row(3, 0) - EL::d_row(2, 0) == ROW_STEP, "");
+        constexpr int MB = (MI >= 2) ? 2 : 1;
+        const int64_t cs_c = SAMPLED ? es.c : 1;   // elements between neighbouring columns of C
+        T *const c_lane = C + (int64_t)row_base * ldc + col_base * cs_c;
+        const int64_t r_step = (int64_t)ROW_STEP * ldc, mi_step = 16 * ldc;
+        // Four forms, chosen once per workgroup: alpha = beta = 1 (the paper's own operation: one addition
+        // per element) with the addition done by the lane or, on request of the host, by the memory system
+        // (no-return floating-point atomics: each element belongs to one lane, so it is the same single rounding);
+        // beta = 0 (C is not read); and the general one.
+        constexpr int kUnit = 0, kOverwrite = 1, kScaled = 2, kUnitAtomic = 3;
+        auto epilogue = [&](auto kind_tag) {
+            constexpr int KIND = decltype(kind_tag)::value;
+            constexpr bool UNIT = KIND == kUnit;
+            constexpr bool read_c = KIND != kOverwrite;
+            T *c_mb = c_lane;
+            if constexpr (KIND == kUnitAtomic) {
+    #pragma unroll
+                for (int mi = 0; mi < MI; ++mi) {
+                    T *c_r = c_mb;
+    #pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int row = row_base + mi * 16 + r * ROW_STEP;
+    #pragma unroll
+                        for (int ni = 0; ni < NI; ++ni) {
+                            const int col = col_base + ni * 16;
+                            if (!GENERIC || tile_full || (row < M && col < N)) unsafeAtomicAdd(&c_r[ni * 16 * cs_c], acc[mi][ni][r]);
+                        }
+                        c_r += r_step;
                     }
-                    c_r += r_step;
+                    c_mb += mi_step;
                 }
-                c_mi += mi_step;
+                return;
             }
-            c_mi = c_mb;
-#pragma unroll
-            for (int mi = mb; mi < mb + MB; ++mi) {
-                T *c_r = c_mi;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = row_base + mi * 16 + r * ROW_STEP;
-#pragma unroll
-                    for (int ni = 0; ni < NI; ++ni) {
-                        const int col = col_base + ni * 16;
-                        if (!GENERIC || tile_full || (row < M && col < N))
-                            c_r[ni * 16 * cs_c] = UNIT ? cin[mi - mb][ni][r] + acc[mi][ni][r]
-                                                : scaled_update(alpha, acc[mi][ni][r], beta, cin[mi - mb][ni][r], read_c);
+    #pragma unroll
+            for (int mb = 0; mb < MI; mb += MB) {
+                T cin[MB][NI][4];
+                T *c_mi = c_mb;
+    #pragma unroll
+                for (int mi = mb; mi < mb + MB; ++mi) {
+                    T *c_r = c_mi;
+    #pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int row = row_base + mi * 16 + r * ROW_STEP;
+    #pragma unroll
+                        for (int ni = 0; ni < NI; ++ni) {
+                            const int col = col_base + ni * 16;
+                            if (read_c && (!GENERIC || tile_full || (row < M && col < N))) cin[mi - mb][ni][r] = c_r[ni * 16 * cs_c];
+                            else cin[mi - mb][ni][r] = T(0);
+                        }
+                        c_r += r_step;
                     }
-                    c_r += r_step;
+                    c_mi += mi_step;
                 }
-                c_mi += mi_step;
+                c_mi = c_mb;
+    #pragma unroll
+                for (int mi = mb; mi < mb + MB; ++mi) {
+                    T *c_r = c_mi;
+    #pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int row = row_base + mi * 16 + r * ROW_STEP;
+    #pragma unroll
+                        for (int ni = 0; ni < NI; ++ni) {
+                            const int col = col_base + ni * 16;
+                            if (!GENERIC || tile_full || (row < M && col < N))
+                                c_r[ni * 16 * cs_c] = UNIT ? cin[mi - mb][ni][r] + acc[mi][ni][r]
+                                                    : scaled_update(alpha, acc[mi][ni][r], beta, cin[mi - mb][ni][r], read_c);
+                        }
+                        c_r += r_step;
+                    }
+                    c_mi += mi_step;
+                }
+                c_mb += MB * mi_step;
             }
-            c_mb += MB * mi_step;
-        }
     };
-    if (alpha == T(1) && beta == T(1)) epilogue(std::integral_constant<int, kUnit>{});
+    if (alpha == T(1) && beta == T(1) && (split.flags & kFlagAtomicC)) epilogue(std::integral_constant<int, kUnitAtomic>{});
+    else if (alpha == T(1) && beta == T(1)) epilogue(std::integral_constant<int, kUnit>{});
     else if (beta == T(0)) epilogue(std::integral_constant<int, kOverwrite>{});
     else epilogue(std::integral_constant<int, kScaled>{});
+    };
+
+    int s = 0;
+    for (; s + 1 < nk; s += 2) {
+        iteration(s, std::integral_constant<int, 0>{});
+        iteration(s + 1, std::integral_constant<int, 1>{});
+    }
+    if (s < nk) iteration(s, std::integral_constant<int, 0>{});
+    GEMM_PHASE_MARK(4);
+    write_tile();
+    GEMM_PHASE_MARK(5);
+    GEMM_PHASE_CLOCK(2);
 }
 
 // Reference-shaped kernel without tiling or staging: one thread per element of C, k ascending.

@@ -1,0 +1,101 @@
+"""The two ways the double-precision kernels update C when alpha == beta == 1 (load-add-store by the lane, or additions
+performed by the memory system) must give the same bits, special values included, and the automatic choice must fall
+back to the first for memory that is not ordinary device memory (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2003_00532_amd import binding, synth
+
+import gpu_util
+import pins
+
+pytestmark = pytest.mark.gpu
+LOAD_STORE, IN_MEMORY = 1, 2
+
+
+@pytest.fixture
+def epilogue_mode():
+    prev = binding.gemm_f64_set_epilogue_mode(0)
+    yield binding.gemm_f64_set_epilogue_mode
+    binding.gemm_f64_set_epilogue_mode(prev)
+
+
+def _run(mode, set_mode, Ab, Bb, Cb, M, N, K, variant):
+    set_mode(mode)
+    try:
+        return gpu_util.run_device(Ab, Bb, Cb, M, N, K, variant=variant)[2]
+    finally:
+        set_mode(0)
+
+
+def _same_bits_or_both_nan(x, y, what):
+    nan = np.isnan(x)
+    assert np.array_equal(nan, np.isnan(y)), what + ": NaN in different places"
+    bad = np.flatnonzero((x.view(np.uint64) != y.view(np.uint64)) & ~nan)
+    assert bad.size == 0, "%s: %d elements differ (first flat index %d: %r vs %r)" % (what, bad.size, bad[0], x.ravel()[bad[0]], y.ravel()[bad[0]])
+
+
+@pytest.mark.parametrize("variant", [-1, 1, 2, 3, 4, 5])
+def test_both_forms_give_the_same_bits_on_uniform_data(gpu_device, epilogue_mode, variant):
+    # ragged and full shapes, padded leading dimensions: every tile kind, edge predicates included
+    for n, (M, N, K) in enumerate([(128, 128, 64), (129, 127, 31), (300, 275, 47), (256, 384, 512), (385, 70, 300)]):
+        Ab, A = synth.matrix(40 + n, synth.TAG_A, M, K, K + 2, "uniform")
+        Bb, B = synth.matrix(40 + n, synth.TAG_B, K, N, N + 4, "uniform")
+        Cb, C0 = synth.matrix(40 + n, synth.TAG_C, M, N, N + 3, "uniform")
+        c_ls = _run(LOAD_STORE, epilogue_mode, Ab, Bb, Cb, M, N, K, variant)
+        c_im = _run(IN_MEMORY, epilogue_mode, Ab, Bb, Cb, M, N, K, variant)
+        what = "variant %d %s" % (variant, (M, N, K))
+        assert synth.padding_intact(c_im, N), what + ": padding written by the in-memory form"
+        pins.assert_bitwise(c_im, c_ls, what)
+        gpu_util.check_against_oracle(A, B, C0, c_im[:, :N], False, what)
+
+
+def test_both_forms_agree_on_special_values(gpu_device, epilogue_mode):
+    # C holds infinities, NaN, signed zeros, subnormals and the largest finite values; the sums include exact zeros
+    # (zero rows of A), subnormal sums (tiny operands), overflowing sums and infinities
+    M, N, K = 192, 160, 48
+    rng = np.random.default_rng(3)
+    A = rng.uniform(-1, 1, (M, K)); B = rng.uniform(-1, 1, (K, N))
+    A[0:16, :] = 0.0                      # sums of +0 products: exact +0
+    A[16:32, :] *= 2.0 ** -505; B[:, 0:40] *= 2.0 ** -505   # rows 16..31 x columns 0..39: sums around 2^-1010, next to the subnormal values of C
+    A[32:48, :] *= 2.0 ** 600; B[:, 40:80] *= 2.0 ** 500    # overflow to infinity
+    A[48, 3] = np.inf
+    specials = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 5e-324, -5e-324, 2.0 ** -1040, -(2.0 ** -1040), 2.0 ** -1022,
+                         np.finfo(np.float64).max, -np.finfo(np.float64).max, 1.0, -1.0, 2.0 ** -1080, 3.0 * 2.0 ** -1075])
+    C0 = specials[rng.integers(0, len(specials), (M, N))]
+    for variant in (-1, 1, 2, 4, 5):
+        c_ls = _run(LOAD_STORE, epilogue_mode, A, B, C0.copy(), M, N, K, variant)
+        c_im = _run(IN_MEMORY, epilogue_mode, A, B, C0.copy(), M, N, K, variant)
+        _same_bits_or_both_nan(c_im, c_ls, "special values, variant %d" % variant)
+        # rows of zeros in A leave C as it was (its subnormal values included: the addition does not flush them),
+        # except that -0 + (+0) is +0
+        want = C0[0:16].copy(); want[(want == 0)] = 0.0
+        _same_bits_or_both_nan(np.ascontiguousarray(c_im[0:16]), want, "zero rows, variant %d" % variant)
+        assert np.any((np.abs(want) > 0) & (np.abs(want) < 2.0 ** -1022)), "the zero rows were meant to meet subnormal values of C"
+
+
+def test_automatic_choice_and_host_memory(gpu_device, epilogue_mode):
+    # K >= 256 and 2^20 outputs: the automatic rule takes the in-memory form for device memory.  For C in page-locked
+    # host memory mapped into the device it must not (such additions are not defined there), also when forced.
+    M = N = 1024
+    K = 256
+    Ab, Bb, Cb = (synth.matrix(5, t, r, c, None, "int")[0] for t, r, c in ((synth.TAG_A, M, K), (synth.TAG_B, K, N), (synth.TAG_C, M, N)))
+    want = Cb.copy()
+    oracle.gemm_f64_ref(Ab, Bb, want)
+    dA, dB = gpu_util.to_dev(Ab), gpu_util.to_dev(Bb)
+    for mode in (0, IN_MEMORY, LOAD_STORE):
+        epilogue_mode(mode)
+        dC = gpu_util.to_dev(Cb)
+        binding.gemm_f64(M, N, K, dA, K, dB, N, dC, N)
+        torch.cuda.synchronize()
+        pins.assert_bitwise(dC.cpu().numpy(), want, "device C, mode %d" % mode)
+        hC = torch.empty((M, N), dtype=torch.float64, pin_memory=True)
+        hC.copy_(torch.from_numpy(Cb))
+        binding.gemm_f64(M, N, K, dA, K, dB, N, hC.data_ptr(), N)
+        torch.cuda.synchronize()
+        pins.assert_bitwise(hC.numpy(), want, "page-locked host C, mode %d" % mode)
+    epilogue_mode(0)
+    with pytest.raises(binding.GemmF64Error):
+        binding.gemm_f64_set_epilogue_mode(7)

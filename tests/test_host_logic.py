@@ -93,6 +93,34 @@ def test_tile_mapping_is_a_bijection(tiles):
         binding.gemm_f64_tile_of_block(tm * tn, tm, tn)
 
 
+def _tile_of_block_by_division(b, tiles_m, tiles_n):
+    """The grouped order written with plain integer divisions (the library multiplies by host-prepared reciprocals)."""
+    total = tiles_m * tiles_n
+    per, rem = divmod(total, 8)
+    x, s = b % 8, b // 8
+    logical = x * per + min(x, rem) + s
+    width = 8 * tiles_n
+    g = logical // width
+    first_m = g * 8
+    gsz = min(tiles_m - first_m, 8)
+    in_g = logical - g * width
+    tn = in_g // gsz
+    return first_m + in_g - tn * gsz, tn
+
+
+def test_tile_mapping_equals_its_definition_by_division():
+    import random
+    rnd = random.Random(5)
+    shapes = [(1, 1), (7, 1), (1, 7), (8, 3), (9, 3), (15, 17), (16, 16), (17, 17), (33, 33), (66, 33), (128, 256), (256, 128),
+              (129, 255), (1000, 3), (3, 1000), (1, 65536), (65536, 1), (46340, 46340), (7, 306783378), (306783378, 7)]
+    for tm, tn in shapes:
+        total = tm * tn
+        assert total < 2 ** 31
+        blocks = set(range(min(total, 300))) | {total - 1 - i for i in range(min(total, 300))} | {rnd.randrange(total) for _ in range(400)}
+        for b in blocks:
+            assert binding.gemm_f64_tile_of_block(b, tm, tn) == _tile_of_block_by_division(b, tm, tn), (b, tm, tn)
+
+
 def test_tile_mapping_keeps_an_xcd_compact():
     # 64x64 tiles (8192^2 at 128x128): the first 64 workgroups of each XCD (two per compute unit,
     # 32 compute units) must form an 8x8 patch, i.e. share 8 A panels and 8 B panels
