@@ -69,8 +69,8 @@ int gemm_f32_strided(int64_t M, int64_t N, int64_t K,
                      float beta, float *C, int64_t rsc, int64_t csc,
                      void *stream);
 
-/* The float counterparts of gemm_f64_general_ws, gemm_f64_split_k_plan and gemm_f64_split_k_workspace_bytes
- * (workspace 4-byte aligned, slice lengths multiples of 32). */
+/* The float counterparts of gemm_f64_general_ws, gemm_f64_split_k_plan, gemm_f64_tail_split_plan and
+ * gemm_f64_split_k_workspace_bytes (workspace 4-byte aligned, slice lengths multiples of 32). */
 int gemm_f32_general_ws(int transa, int transb, int64_t M, int64_t N, int64_t K,
                         float alpha, const float *A, int64_t lda,
                         const float *B, int64_t ldb,
@@ -78,6 +78,8 @@ int gemm_f32_general_ws(int transa, int transb, int64_t M, int64_t N, int64_t K,
                         void *workspace, int64_t workspace_bytes, void *stream);
 int gemm_f32_split_k_plan(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu,
                           int64_t workspace_bytes, int *variant, int *splits, int *k_chunk);
+int gemm_f32_tail_split_plan(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu,
+                             int64_t workspace_bytes, int *variant, int *tail_tiles, int *tail_splits, int *tail_k_chunk);
 int64_t gemm_f32_split_k_workspace_bytes(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu);
 
 /* Variant table of the float kernels ("mfma_128x128x32", ...) and the host-side selection rule

@@ -200,8 +200,9 @@ int gemm_f64_strided_path(int64_t M, int64_t N, int64_t K,
  * few output tiles and a long k range the library may cut the range into S slices, compute the S partial products
  * into S dense M x N slabs of the workspace with one launch, and add them up in ascending order in a second launch
  * (the result is a pure function of the arguments and of the workspace size on offer, never of scheduling).
- * Whether and how it splits is decided by gemm_f64_split_k_plan; with workspace == NULL, with too little of it or
- * when splitting would not pay, the call is gemm_f64_general exactly.
+ * Whether and how it splits is decided by gemm_f64_split_k_plan; a problem that is not split that way may instead have
+ * only its last few tiles computed in slices (gemm_f64_tail_split_plan); with workspace == NULL, with too little of it
+ * or when neither would pay, the call is gemm_f64_general exactly.
  *
  *   workspace        device pointer, 8-byte aligned, workspace_bytes long; owned by the caller, used only between
  *                    the two launches of this call on `stream`, contents undefined afterwards; calls that share a
@@ -253,7 +254,22 @@ int gemm_f64_general_static(int transa, int transb, int64_t M, int64_t N, int64_
 int gemm_f64_split_k_plan(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu,
                           int64_t workspace_bytes, int *variant, int *splits, int *k_chunk);
 
-/* Bytes of workspace the rule would use if it could have any amount (0: it would not split this problem). */
+/*
+ * gemm_f64_tail_split_plan: the other use gemm_f64_general_ws makes of a workspace, again a pure host-side rule (the
+ * partial-tile question of the paper's Section 2.15 Q2 at the level of the whole chip).  Workgroups run in rounds of
+ * (compute units x resident workgroups); when the tiles of a problem make up whole rounds plus a small rest, that rest
+ * would occupy a few compute units for the time of a whole tile.  Instead the last *tail_tiles tiles of the tile order
+ * are computed in *tail_splits slices of the k range, *tail_k_chunk long each (a multiple of 16), into dense slabs of
+ * the workspace, by extra workgroups of the same launch; a second, small launch adds the slabs of each tile in
+ * ascending order and applies alpha and beta.  *tail_tiles == 0: no tail split (also whenever the k range of the whole
+ * problem is split instead, see gemm_f64_split_k_plan; the two are never combined).  *variant is the kernel variant
+ * of the call.  Arithmetic of the affected tiles: as for split K.  Returns GEMM_F64_ERR_DIM for negative sizes or
+ * bad flags.  Output pointers may be NULL.
+ */
+int gemm_f64_tail_split_plan(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu,
+                             int64_t workspace_bytes, int *variant, int *tail_tiles, int *tail_splits, int *tail_k_chunk);
+
+/* Bytes of workspace the two rules together would use if they could have any amount (0: neither applies). */
 int64_t gemm_f64_split_k_workspace_bytes(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu);
 
 /*

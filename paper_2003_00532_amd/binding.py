@@ -78,6 +78,9 @@ def load():
     for fn in (lib.gemm_f64_split_k_plan, lib.gemm_f32_split_k_plan):
         fn.argtypes = [ci, ci, i64, i64, i64, ci, i64, ip, ip, ip]
         fn.restype = ci
+    for fn in (lib.gemm_f64_tail_split_plan, lib.gemm_f32_tail_split_plan):
+        fn.argtypes = [ci, ci, i64, i64, i64, ci, i64, ip, ip, ip, ip]
+        fn.restype = ci
     for fn in (lib.gemm_f64_split_k_workspace_bytes, lib.gemm_f32_split_k_workspace_bytes):
         fn.argtypes = [ci, ci, i64, i64, i64, ci]
         fn.restype = i64
@@ -340,6 +343,22 @@ def gemm_f64_split_k_plan(transa, transb, M, N, K, num_cu=256, workspace_bytes=2
 
 def gemm_f32_split_k_plan(transa, transb, M, N, K, num_cu=256, workspace_bytes=2 ** 62):
     return _plan(load().gemm_f32_split_k_plan, transa, transb, M, N, K, num_cu, workspace_bytes)
+
+
+def _tail_plan(fn, transa, transb, M, N, K, num_cu, workspace_bytes):
+    v, t, s, c = (ctypes.c_int(-1) for _ in range(4))
+    _check(fn(int(transa), int(transb), M, N, K, int(num_cu), int(workspace_bytes), ctypes.byref(v), ctypes.byref(t),
+              ctypes.byref(s), ctypes.byref(c)))
+    return int(v.value), int(t.value), int(s.value), int(c.value)
+
+
+def gemm_f64_tail_split_plan(transa, transb, M, N, K, num_cu=256, workspace_bytes=2 ** 62):
+    """(variant, tail tiles, slices per tail tile, slice length) of a call with this much workspace; 0 tiles: no tail split."""
+    return _tail_plan(load().gemm_f64_tail_split_plan, transa, transb, M, N, K, num_cu, workspace_bytes)
+
+
+def gemm_f32_tail_split_plan(transa, transb, M, N, K, num_cu=256, workspace_bytes=2 ** 62):
+    return _tail_plan(load().gemm_f32_tail_split_plan, transa, transb, M, N, K, num_cu, workspace_bytes)
 
 
 def gemm_f64_split_k_workspace_bytes(transa, transb, M, N, K, num_cu=256) -> int:

@@ -94,7 +94,22 @@ extern "C" int gemm_f32_split_k_plan(int transa, int transb, int64_t M, int64_t 
 
 extern "C" int64_t gemm_f32_split_k_workspace_bytes(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu)
 {
-    int splits = 1;
-    if (gemm_f32_split_k_plan(transa, transb, M, N, K, num_cu, INT64_MAX, nullptr, &splits, nullptr) != GEMM_F64_OK) return 0;
-    return splits > 1 ? (int64_t)splits * M * N * (int64_t)sizeof(float) : 0;
+    if ((transa != 0 && transa != 1) || (transb != 0 && transb != 1) || M < 0 || N < 0 || K < 0) return 0;
+    if (M > kMaxExtent || N > kMaxExtent || K > kMaxExtent) return 0;
+    const Plan plan = plan_with_workspace(kVariants, kNumVariants, transa, transb, M, N, K, num_cu, (int)sizeof(float), INT64_MAX);
+    return plan_workspace_bytes(kVariants, plan, M, N, (int)sizeof(float));
+}
+
+extern "C" int gemm_f32_tail_split_plan(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu, int64_t workspace_bytes,
+                                  int *variant, int *tail_tiles, int *tail_splits, int *tail_k_chunk)
+{
+    if ((transa != 0 && transa != 1) || (transb != 0 && transb != 1) || M < 0 || N < 0 || K < 0 || workspace_bytes < 0)
+        return GEMM_F64_ERR_DIM;
+    if (M > kMaxExtent || N > kMaxExtent || K > kMaxExtent) return GEMM_F64_ERR_TOO_LARGE;
+    const Plan plan = plan_with_workspace(kVariants, kNumVariants, transa, transb, M, N, K, num_cu, (int)sizeof(float), workspace_bytes);
+    if (variant) *variant = plan.variant;
+    if (tail_tiles) *tail_tiles = plan.splits > 1 ? 0 : plan.tail_tiles;
+    if (tail_splits) *tail_splits = plan.splits > 1 ? 1 : plan.tail_splits;
+    if (tail_k_chunk) *tail_k_chunk = plan.splits > 1 ? 0 : plan.tail_k_chunk;
+    return GEMM_F64_OK;
 }

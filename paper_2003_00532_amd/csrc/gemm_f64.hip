@@ -160,10 +160,10 @@ extern "C" int gemm_f64_general_static(int transa, int transb, int64_t M, int64_
     if (M == 0 || N == 0 || !product)
         return gemm_ex<double>(kVariants, kNumVariants, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, -1);
     // what the rule would like to have when memory is no object
-    const Plan plan = plan_split_k(kVariants, kNumVariants, transa, transb, M, N, K, current_cu_count(), (int)sizeof(double), INT64_MAX);
-    if (plan.splits <= 1)
+    const Plan plan = plan_with_workspace(kVariants, kNumVariants, transa, transb, M, N, K, current_cu_count(), (int)sizeof(double), INT64_MAX);
+    const int64_t wanted = plan_workspace_bytes(kVariants, plan, M, N, (int)sizeof(double));
+    if (wanted == 0)
         return gemm_ex<double>(kVariants, kNumVariants, transa, transb, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, stream, -1);
-    const int64_t wanted = (int64_t)plan.splits * M * N * (int64_t)sizeof(double);
     if (wanted > GEMM_F64_STATIC_SCRATCH_BYTES) return GEMM_F64_ERR_SCRATCH;
     void *ptr = scratch_on_current_device();
     if (ptr == nullptr) return GEMM_F64_ERR_SCRATCH;
@@ -212,9 +212,24 @@ extern "C" int gemm_f64_split_k_plan(int transa, int transb, int64_t M, int64_t 
 
 extern "C" int64_t gemm_f64_split_k_workspace_bytes(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu)
 {
-    int splits = 1;
-    if (gemm_f64_split_k_plan(transa, transb, M, N, K, num_cu, INT64_MAX, nullptr, &splits, nullptr) != GEMM_F64_OK) return 0;
-    return splits > 1 ? (int64_t)splits * M * N * (int64_t)sizeof(double) : 0;
+    if ((transa != 0 && transa != 1) || (transb != 0 && transb != 1) || M < 0 || N < 0 || K < 0) return 0;
+    if (M > kMaxExtent || N > kMaxExtent || K > kMaxExtent) return 0;
+    const Plan plan = plan_with_workspace(kVariants, kNumVariants, transa, transb, M, N, K, num_cu, (int)sizeof(double), INT64_MAX);
+    return plan_workspace_bytes(kVariants, plan, M, N, (int)sizeof(double));
+}
+
+extern "C" int gemm_f64_tail_split_plan(int transa, int transb, int64_t M, int64_t N, int64_t K, int num_cu, int64_t workspace_bytes,
+                                  int *variant, int *tail_tiles, int *tail_splits, int *tail_k_chunk)
+{
+    if ((transa != 0 && transa != 1) || (transb != 0 && transb != 1) || M < 0 || N < 0 || K < 0 || workspace_bytes < 0)
+        return GEMM_F64_ERR_DIM;
+    if (M > kMaxExtent || N > kMaxExtent || K > kMaxExtent) return GEMM_F64_ERR_TOO_LARGE;
+    const Plan plan = plan_with_workspace(kVariants, kNumVariants, transa, transb, M, N, K, num_cu, (int)sizeof(double), workspace_bytes);
+    if (variant) *variant = plan.variant;
+    if (tail_tiles) *tail_tiles = plan.splits > 1 ? 0 : plan.tail_tiles;
+    if (tail_splits) *tail_splits = plan.splits > 1 ? 1 : plan.tail_splits;
+    if (tail_k_chunk) *tail_k_chunk = plan.splits > 1 ? 0 : plan.tail_k_chunk;
+    return GEMM_F64_OK;
 }
 
 extern "C" int gemm_f64_set_epilogue_mode(int mode)

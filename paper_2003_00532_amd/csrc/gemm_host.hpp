@@ -100,7 +100,18 @@ struct Plan {
     int variant;
     int splits;     // 1: no split
     int k_chunk;    // slice length, a multiple of the stage depth (K itself when splits == 1)
+    // Tail split (splits == 1 only): the last tail_tiles tiles of the grouped order are computed in tail_splits
+    // slices of tail_k_chunk each; 0 tiles: none.
+    int tail_tiles = 0, tail_splits = 1, tail_k_chunk = 0;
 };
+
+// Bytes of workspace a plan uses.
+inline int64_t plan_workspace_bytes(const Variant *variants, const Plan &p, int64_t M, int64_t N, int elem_bytes)
+{
+    if (p.splits > 1) return (int64_t)p.splits * M * N * elem_bytes;
+    if (p.tail_tiles > 0) return (int64_t)p.tail_tiles * p.tail_splits * variants[p.variant].bm * variants[p.variant].bn * elem_bytes;
+    return 0;
+}
 
 inline Plan plan_split_k(const Variant *variants, int count, int transa, int transb, int64_t M, int64_t N, int64_t K,
                          int num_cu, int elem_bytes, int64_t workspace_bytes)
@@ -130,6 +141,62 @@ inline Plan plan_split_k(const Variant *variants, int count, int transa, int tra
 // The kernels hold extents and tile origins in 32-bit integers and form "origin + tile size" and "extent + stage
 // depth - 1" in them; the largest tile is 128 wide and the deepest stage 32, so extents up to 2^31 - 1 - 128 are safe.
 constexpr int64_t kMaxExtent = (int64_t)INT32_MAX - 128;
+
+// Tail split.  Workgroups are dispatched in rounds of (compute units x resident workgroups) slots; when the tiles of
+// a problem make up some whole rounds and a small rest, the rest occupies a few compute units for the time of a whole
+// tile while the others idle (2088 x 2049 x 2047 with 64 x 64 tiles: 1089 tiles on 1024 slots, the last 65 tiles run
+// alone).  With a workspace the k range of just those last tiles is cut into S slices so that tail * S units fill one
+// round of slots, each a fraction 1/S of a tile long; their slabs are added in a second, small launch.  The plan prices
+// every variant that way with the model of variant_cost and keeps the cheapest if it beats the unsplit choice by 3 %.
+inline Plan plan_tail_split(const Variant *variants, int count, int transa, int transb, int64_t M, int64_t N, int64_t K,
+                            int num_cu, int elem_bytes, int64_t workspace_bytes, const Plan &unsplit, double unsplit_cost)
+{
+    Plan best = unsplit;
+    if (M <= 0 || N <= 0 || K <= 0 || workspace_bytes <= 0) return best;
+    const int bk = 8 * (16 / elem_bytes);
+    const double slot_seconds = (elem_bytes == 8 ? 64.0 : 32.0) / 2.4e9;
+    double best_cost = unsplit_cost * 0.97;
+    const int64_t nk = ceil_div(K, bk);
+    for (int v = 1; v < count; ++v) {
+        const Variant &var = variants[v];
+        if (!variant_available(var, transa, transb)) continue;
+        const int64_t tiles = ceil_div(M, var.bm) * ceil_div(N, var.bn);
+        const int64_t slots = (int64_t)num_cu * var.resident;
+        if (tiles <= slots || tiles > INT32_MAX) continue;   // fewer tiles than slots is the business of split K
+        const int64_t rounds = tiles / slots, tail = tiles % slots;
+        if (tail == 0) continue;
+        int64_t s = slots / tail;
+        if (s > 32) s = 32;
+        if (s > nk) s = nk;
+        if (s < 2) continue;
+        const int64_t chunk_stages = ceil_div(nk, s);
+        const int64_t slices = ceil_div(nk, chunk_stages);
+        if (slices < 2) continue;
+        const int64_t bytes = tail * slices * var.bm * var.bn * elem_bytes;
+        if (bytes > workspace_bytes) continue;
+        const double wave_chain = (double)(var.bm / 32) * (var.bn / 32);
+        const double tile_cost = wave_chain * (double)ceil_div(K, 4) / var.efficiency + var.overhead;
+        const double unit_cost = wave_chain * (double)(chunk_stages * bk / 4) / var.efficiency + var.overhead;
+        const double reduce = ((double)(slices + 2) * tail * var.bm * var.bn * elem_bytes / 2.5e12 + 4e-6) / slot_seconds;
+        const double cost = (double)(rounds * var.resident) * tile_cost + (double)ceil_div(tail * slices, num_cu) * unit_cost + reduce;
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = Plan{v, 1, (int)K, (int)tail, (int)slices, (int)(chunk_stages * bk)};
+        }
+    }
+    return best;
+}
+
+// What a call with a workspace on offer does: split K, or a tail split, or neither.
+inline Plan plan_with_workspace(const Variant *variants, int count, int transa, int transb, int64_t M, int64_t N, int64_t K,
+                                int num_cu, int elem_bytes, int64_t workspace_bytes)
+{
+    const Plan split = plan_split_k(variants, count, transa, transb, M, N, K, num_cu, elem_bytes, workspace_bytes);
+    if (split.splits > 1) return split;
+    double cost = 0.0;
+    choose_variant(variants, count, transa, transb, M, N, K < 1 ? 1 : K, num_cu, 1, &cost);
+    return plan_tail_split(variants, count, transa, transb, M, N, K, num_cu, elem_bytes, workspace_bytes, split, cost);
+}
 
 // Stored shapes: A is M x K (K x M when transa), B is K x N (N x K when transb), C is M x N; a leading
 // dimension must cover the stored row.  A and B are only required when the product is formed
@@ -186,6 +253,9 @@ struct Job {
     // cover a row; such a job runs in the kSampled mode (64 x 64 tile only) whatever its other properties.
     bool sampled = false;
     ElemStrides es{1, 1, 1};
+    // Tail split: the last tail_tiles tiles of the grouped order in tail_splits slices of tail_k_chunk, into `slabs`
+    int tail_tiles = 0, tail_splits = 1, tail_k_chunk = 0;
+    T *slabs = nullptr;
 };
 
 template <typename T, int BM, int BN, int WM, int WN, bool TA, bool TB>
@@ -196,14 +266,21 @@ hipError_t launch_mfma_t(const Job<T> &j)
     const int64_t tiles = (int64_t)tiles_m * tiles_n;
     const bool vec = async_copies_possible<T>(j.lda, j.ldb);
     // The lean kernel assumes full tiles everywhere and whole K stages (in every slice).
-    const bool lean = !j.sampled && vec && (j.M % BM == 0) && (j.N % BN == 0) && (j.K % BK == 0) && (j.split.k_chunk % BK == 0);
-    const dim3 grid((unsigned)tiles, (unsigned)j.slices), block(kThreads);
-    const TileMap map = make_tile_map((uint32_t)tiles_m, (uint32_t)tiles_n);
+    const bool lean = !j.sampled && vec && (j.M % BM == 0) && (j.N % BN == 0) && (j.K % BK == 0) && (j.split.k_chunk % BK == 0) &&
+                      (j.tail_k_chunk % BK == 0);
+    const int64_t whole = tiles - j.tail_tiles;   // tiles computed over the whole k range, one block each
+    const dim3 grid((unsigned)(whole + (int64_t)j.tail_tiles * j.tail_splits), (unsigned)j.slices), block(kThreads);
+    const TileMap map = make_tile_map((uint32_t)tiles_m, (uint32_t)tiles_n, (uint32_t)whole);
+    TailSplit tail = no_tail();
+    if (j.tail_tiles > 0)
+        tail = TailSplit{(uint32_t)whole, make_fast_div((uint32_t)j.tail_splits), j.tail_k_chunk,
+                         j.transa ? (int64_t)j.tail_k_chunk * j.lda : (int64_t)j.tail_k_chunk,
+                         j.transb ? (int64_t)j.tail_k_chunk : (int64_t)j.tail_k_chunk * j.ldb, j.slabs};
     if (j.sampled) {
         // built for one tile shape only (the mode needs more registers than the largest tile leaves)
         if constexpr (BM == 64 && BN == 64) {
             hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kSampled, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
-                               j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, map, j.split, j.es);
+                               j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, map, j.split, j.es, tail);
             return hipGetLastError();
         } else {
             return hipErrorInvalidValue;
@@ -211,13 +288,13 @@ hipError_t launch_mfma_t(const Job<T> &j)
     }
     if (lean)
         hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kLean, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
-                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, map, j.split, j.es);
+                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, map, j.split, j.es, tail);
     else if (vec)
         hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kGeneric, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
-                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, map, j.split, j.es);
+                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, map, j.split, j.es, tail);
     else
         hipLaunchKernelGGL((gemm_mfma_kernel<T, BM, BN, WM, WN, kStaged, TA, TB>), grid, block, 0, j.stream, j.M, j.N, j.K,
-                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, map, j.split, j.es);
+                           j.alpha, j.A, j.lda, j.B, j.ldb, j.beta, j.C, j.ldc, map, j.split, j.es, tail);
     return hipGetLastError();
 }
 
@@ -332,8 +409,8 @@ int gemm_ex(const Variant *variants, int count, int transa, int transb, int64_t 
     Job<T> job{transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, stream, 1, SplitK{k, 0, 0, 0}};
     job.split.flags = accumulate_in_memory<T>(M, N, K, alpha, beta, C) ? kFlagAtomicC : 0;
     if (variant == -1) {
-        const Plan plan = plan_split_k(variants, count, transa, transb, M, N, K, current_cu_count(), (int)sizeof(T),
-                                       workspace ? workspace_bytes : 0);
+        const Plan plan = plan_with_workspace(variants, count, transa, transb, M, N, K, current_cu_count(), (int)sizeof(T),
+                                              workspace ? workspace_bytes : 0);
         variant = plan.variant;
         if (plan.splits > 1) {
             // first step: slice y of the k range into slab y of the workspace (dense M x N), nothing scaled yet
@@ -350,6 +427,24 @@ int gemm_ex(const Variant *variants, int count, int transa, int transb, int64_t 
             // second step: C <- alpha * (sum of the slabs, in order) + beta * C
             const dim3 grid((unsigned)ceil_div(M * N, 256)), block(256);
             hipLaunchKernelGGL(split_k_reduce_kernel<T>, grid, block, 0, stream, m, n, plan.splits, alpha, slabs, beta, C, ldc);
+            return hipGetLastError() == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
+        }
+        if (plan.tail_tiles > 0) {
+            // one launch computes the tiles of the whole rounds into C and the last tiles, in slices, into slabs of the
+            // workspace; a second, small one adds each tile's slabs in order and applies alpha and beta
+            const Variant &var = variants[variant];
+            T *slabs = static_cast<T *>(workspace);
+            job.tail_tiles = plan.tail_tiles;
+            job.tail_splits = plan.tail_splits;
+            job.tail_k_chunk = plan.tail_k_chunk;
+            job.slabs = slabs;
+            err = launch_variant<T>(variant, job);
+            if (err != hipSuccess) return GEMM_F64_ERR_LAUNCH;
+            const uint32_t tiles_m = (uint32_t)ceil_div(M, var.bm), tiles_n = (uint32_t)ceil_div(N, var.bn);
+            const uint32_t whole = tiles_m * tiles_n - (uint32_t)plan.tail_tiles;
+            const dim3 grid((unsigned)((int64_t)plan.tail_tiles * (var.bm * var.bn / 256))), block(256);
+            hipLaunchKernelGGL(tail_reduce_kernel<T>, grid, block, 0, stream, m, n, var.bm, var.bn,
+                               make_tile_map(tiles_m, tiles_n, whole), whole, plan.tail_splits, alpha, slabs, beta, C, ldc);
             return hipGetLastError() == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
         }
     } else if (variant > 0 && !variant_available(variants[variant], transa, transb)) {

@@ -149,9 +149,11 @@ struct TileMap {
     FastDiv last;          // height of the last group (tiles_m % kGroupM, or kGroupM)
 };
 
-inline TileMap make_tile_map(uint32_t tiles_m, uint32_t tiles_n)
+// `blocks` is the number of leading positions of the order that are dealt to the XCDs this way (all of them, unless
+// the last ones are computed in slices, see TailSplit).
+inline TileMap make_tile_map(uint32_t tiles_m, uint32_t tiles_n, uint32_t blocks = 0)
 {
-    const uint32_t total = tiles_m * tiles_n;
+    const uint32_t total = blocks ? blocks : tiles_m * tiles_n;
     const uint32_t last = tiles_m % kGroupM ? tiles_m % kGroupM : kGroupM;
     return TileMap{tiles_m, tiles_n, total / kXcds, total % kXcds, make_fast_div(kGroupM * tiles_n), make_fast_div(last)};
 }
@@ -181,6 +183,21 @@ __host__ __device__ inline void tile_of_block(uint32_t b, const TileMap &map, ui
 {
     tile_at(position_of_block(b, map), map, tm, tn);
 }
+
+// Tail split.  A launch whose tiles do not fill the chip's workgroup slots in whole rounds leaves the last, partial
+// round to a few compute units.  With a workspace the host can cut the k range of just those last tiles: blocks
+// 0 .. begin-1 compute whole tiles as usual (positions 0 .. begin-1 of the grouped order), and every later block is
+// one slice of one of the remaining tiles: unit u = block - begin computes slice u % S of the tile at position
+// begin + u / S into its own dense BM x BN slab, slab u of `slabs`; a second launch adds the slabs of each tile in
+// ascending order and applies alpha, beta (tail_reduce_kernel).  begin == UINT32_MAX: no tail.
+struct TailSplit {
+    uint32_t begin;
+    FastDiv splits;            // S
+    int k_chunk;               // slice length, a multiple of the stage depth
+    int64_t step_a, step_b;    // what one slice adds, in elements, to the pointers of A and B
+    void *slabs;
+};
+inline TailSplit no_tail() { return TailSplit{UINT32_MAX, FastDiv{1, 0, 0}, 0, 0, 0, nullptr}; }
 
 // Workgroup barrier that also publishes this wave's LDS traffic: every LDS read, LDS write and
 // asynchronous global->LDS load the wave has issued is complete before it arrives.  Written as one
@@ -455,18 +472,24 @@ struct Panel {
 // tiles: it then schedules the K loop differently; the smaller tiles fit more waves anyway.)
 template <typename T, int BM, int BN, int WM, int WN, int MODE, bool TA, bool TB>
 __global__ void __launch_bounds__(kThreads, 2)
-gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, int64_t lda, const T *__restrict__ B_,
-                 int64_t ldb, T beta, T *__restrict__ C_, int64_t ldc, TileMap map, SplitK split, ElemStrides es)
+gemm_mfma_kernel(int M, int N, int K_total, T alpha_, const T *__restrict__ A_, int64_t lda, const T *__restrict__ B_,
+                 int64_t ldb, T beta_, T *__restrict__ C_, int64_t ldc_, TileMap map, SplitK split, ElemStrides es, TailSplit tail)
 {
     GEMM_PHASE_MARK(0);
     GEMM_PHASE_CLOCK(1);
     GEMM_PHASE_WHERE();
-    // this workgroup's slice of k (all of it when the grid has height 1)
-    const int slice = blockIdx.y;
-    const int K = min(split.k_chunk, K_total - slice * split.k_chunk);
-    const T *__restrict__ A = A_ + slice * split.step_a;
-    const T *__restrict__ B = B_ + slice * split.step_b;
-    T *__restrict__ C = C_ + slice * split.step_c;
+    // What this workgroup computes: a whole tile (of slice blockIdx.y of k when the grid has a height), or, past
+    // tail.begin, one k slice of one of the last tiles into its own slab (see TailSplit).  Everything here is
+    // wave-uniform and stays on the scalar unit.
+    const bool tail_unit = blockIdx.x >= tail.begin;
+    const uint32_t unit = tail_unit ? blockIdx.x - tail.begin : 0u;
+    const uint32_t unit_tile = fast_div(unit, tail.splits);
+    const int slice = tail_unit ? (int)(unit - unit_tile * tail.splits.d) : (int)blockIdx.y;
+    const int k_chunk = tail_unit ? tail.k_chunk : split.k_chunk;
+    const int K = min(k_chunk, K_total - slice * k_chunk);
+    const T *__restrict__ A = A_ + slice * (tail_unit ? tail.step_a : split.step_a);
+    const T *__restrict__ B = B_ + slice * (tail_unit ? tail.step_b : split.step_b);
+    const T alpha = tail_unit ? T(1) : alpha_, beta = tail_unit ? T(0) : beta_;
     typedef Elem<T> EL;
     typedef typename EL::cell_t cell_t;
     typedef typename EL::acc_t acc_t;
@@ -497,8 +520,12 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha, const T *__restrict__ A_, i
     const int lg = l >> 4, li = l & 15;
 
     uint32_t tm_u, tn_u;
-    tile_of_block(blockIdx.x, map, tm_u, tn_u);
+    tile_at(tail_unit ? tail.begin + unit_tile : position_of_block(blockIdx.x, map), map, tm_u, tn_u);
     const int m0 = (int)tm_u * BM, n0 = (int)tn_u * BN;
+    // the output: C itself, or the slab of this unit addressed as if it were the tile's place in a matrix of BN columns
+    const int64_t ldc = tail_unit ? (int64_t)BN : ldc_;
+    T *__restrict__ C = tail_unit ? static_cast<T *>(tail.slabs) + (int64_t)unit * (BM * BN) - ((int64_t)m0 * BN + n0)
+                                  : C_ + slice * split.step_c;
 
     const bool tile_full = (m0 + BM <= M) && (n0 + BN <= N);
     const int nk = (K + BK - 1) / BK;
@@ -775,6 +802,29 @@ split_k_reduce_kernel(int M, int N, int splits, T alpha, const T *__restrict__ W
     const bool read_c = beta != T(0);
     const T c = read_c ? C[(int64_t)i * ldc + j] : T(0);
     C[(int64_t)i * ldc + j] = scaled_update(alpha, s, beta, c, read_c);
+}
+
+// The second step of a tail split (see TailSplit): for each of the last `tiles` tiles of the grouped order,
+// C_tile <- alpha * (W_0 + ... + W_{S-1}) + beta * C_tile with the S slabs of the tile added in ascending order.
+// One workgroup per 256 consecutive elements of a tile.
+template <typename T>
+__global__ void __launch_bounds__(256)
+tail_reduce_kernel(int M, int N, int bm, int bn, TileMap map, uint32_t begin, int splits, T alpha, const T *__restrict__ W, T beta,
+                   T *__restrict__ C, int64_t ldc)
+{
+    const int per_tile = bm * bn / 256;
+    const uint32_t t = blockIdx.x / per_tile;
+    const int e = (int)(blockIdx.x % per_tile) * 256 + (int)threadIdx.x;
+    uint32_t tm, tn;
+    tile_at(begin + t, map, tm, tn);
+    const int i = (int)tm * bm + e / bn, j = (int)tn * bn + e % bn;
+    if (i >= M || j >= N) return;
+    const T *w = W + (int64_t)t * splits * (bm * bn) + e;
+    T s = w[0];
+    for (int p = 1; p < splits; ++p) s += w[(int64_t)p * (bm * bn)];
+    const bool read_c = beta != T(0);
+    T *c = C + (int64_t)i * ldc + j;
+    *c = scaled_update(alpha, s, beta, read_c ? *c : T(0), read_c);
 }
 
 }  // namespace gemm_detail

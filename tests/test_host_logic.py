@@ -333,7 +333,8 @@ def test_split_k_plan_is_a_consistent_pure_function():
     assert binding.gemm_f64_split_k_plan(0, 0, 128, 128, 65536)[1] > 1
     for (M, N, K) in [(256, 256, 256), (2048, 2048, 2048), (2088, 2049, 2047), (8192, 8192, 8192), (16384, 16384, 256)]:
         assert binding.gemm_f64_split_k_plan(0, 0, M, N, K)[1] == 1
-        assert binding.gemm_f64_split_k_workspace_bytes(0, 0, M, N, K) == 0
+        if (M, N, K) != (2088, 2049, 2047):   # the ragged configuration gets a tail split instead, see below
+            assert binding.gemm_f64_split_k_workspace_bytes(0, 0, M, N, K) == 0
     # the workspace on offer bounds the number of slabs; none at all means no split
     M, N, K = 640, 640, 8192
     want = binding.gemm_f64_split_k_workspace_bytes(0, 0, M, N, K)
@@ -345,6 +346,44 @@ def test_split_k_plan_is_a_consistent_pure_function():
     assert binding.gemm_f64_split_k_plan(0, 0, M, N, K, workspace_bytes=0)[1] == 1
     assert binding.load().gemm_f64_split_k_plan(2, 0, 8, 8, 8, 256, 0, None, None, None) == -1
     assert binding.load().gemm_f64_split_k_plan(0, 0, -1, 8, 8, 256, 0, None, None, None) == -1
+
+
+def test_tail_split_plan_is_a_consistent_pure_function():
+    for plan, ws_bytes, split_plan, nm, isz in (
+            (binding.gemm_f64_tail_split_plan, binding.gemm_f64_split_k_workspace_bytes, binding.gemm_f64_split_k_plan, binding.gemm_f64_variant_name, 8),
+            (binding.gemm_f32_tail_split_plan, binding.gemm_f32_split_k_workspace_bytes, binding.gemm_f32_split_k_plan, binding.gemm_f32_variant_name, 4)):
+        stage = 128 // isz
+        for (M, N, K) in [(2088, 2049, 2047), (2500, 2500, 2500), (4095, 4097, 4095), (2112, 2112, 2048), (4352, 4352, 1024),
+                          (2048, 2048, 2048), (8192, 8192, 8192), (16384, 16384, 256), (256, 256, 256), (640, 640, 8192), (3000, 3000, 40),
+                          (1, 1, 1), (0, 5, 7)]:
+            for ta in (0, 1):
+                for tb in (0, 1):
+                    for cus in (256, 304, 64):
+                        v, tiles, s, chunk = plan(ta, tb, M, N, K, cus)
+                        assert plan(ta, tb, M, N, K, cus) == (v, tiles, s, chunk)
+                        if tiles == 0:
+                            assert s == 1 and chunk == 0
+                            if split_plan(ta, tb, M, N, K, cus)[1] == 1:
+                                assert ws_bytes(ta, tb, M, N, K, cus) == 0
+                            continue
+                        assert split_plan(ta, tb, M, N, K, cus)[1] == 1, "the two splits are never combined"
+                        bm, bn = (int(x) for x in nm(v).split("_")[1].split("x")[:2])
+                        total = -(-M // bm) * -(-N // bn)
+                        assert 0 < tiles < total and 2 <= s <= 32
+                        assert chunk % stage == 0 and (s - 1) * chunk < K <= s * chunk, "every slice has work"
+                        assert ws_bytes(ta, tb, M, N, K, cus) == tiles * s * bm * bn * isz
+                        # the units fit the slots of one round, which is the point of the split
+                        assert tiles * s <= cus * 6
+                        # one byte less than needed: a different plan (or none), never an overrun
+                        v2, t2, s2, c2 = plan(ta, tb, M, N, K, cus, tiles * s * bm * bn * isz - 1)
+                        if t2:
+                            bm2, bn2 = (int(x) for x in nm(v2).split("_")[1].split("x")[:2])
+                            assert t2 * s2 * bm2 * bn2 * isz <= tiles * s * bm * bn * isz - 1
+    # the ragged benchmark configuration is the case it was built for; the others fill whole rounds or are too small
+    assert binding.gemm_f64_tail_split_plan(0, 0, 2088, 2049, 2047)[1:3] == (65, 15)
+    for (M, N, K) in [(256, 256, 256), (2048, 2048, 2048), (8192, 8192, 8192), (16384, 16384, 256)]:
+        assert binding.gemm_f64_tail_split_plan(0, 0, M, N, K)[1] == 0
+    assert binding.load().gemm_f64_tail_split_plan(2, 0, 8, 8, 8, 256, 0, None, None, None, None) == -1
 
 
 def test_workspace_arguments_are_validated_before_any_launch():
