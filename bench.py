@@ -173,6 +173,62 @@ def other_workloads(gemm_ex, choose, variant_name, np_dtype, peak, seed, stream,
     return out
 
 
+STUDY_SHAPES = [(256, 256, 256), (512, 512, 512), (1024, 1024, 1024), (1536, 1536, 1536), (2048, 2048, 2048), (3000, 3000, 3000),
+                (4096, 4096, 4096), (2088, 2049, 2047), (8192, 8192, 8192), (16384, 16384, 256), (1024, 8192, 512),
+                (8192, 1024, 4096), (300, 300, 300), (5000, 200, 3000), (640, 640, 8192), (6144, 6144, 1024), (2304, 2304, 2304)]
+
+
+def selection_study(f32, stream, cus):
+    """How good is the shape-driven variant choice?  Every tiled variant timed on 17 shapes (dense, seeded uniform
+    operands, calls back to back after a warm-up by time); the regret of a shape is the time of the variant the
+    selection rule picks over the time of the best variant, minus one."""
+    import torch
+    from paper_2003_00532_amd import binding
+    gemm_ex = binding.gemm_f32_ex if f32 else binding.gemm_f64_ex
+    choose = binding.gemm_f32_choose_variant if f32 else binding.gemm_f64_choose_variant
+    name = binding.gemm_f32_variant_name if f32 else binding.gemm_f64_variant_name
+    peak = PEAK_FP32_MFMA_TFLOPS if f32 else PEAK_FP64_MFMA_TFLOPS
+    tdt = torch.float32 if f32 else torch.float64
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(0)
+    rows, total = [], 0.0
+    for (M, N, K) in STUDY_SHAPES:
+        dA = torch.rand((M, K), dtype=tdt, device="cuda:0", generator=gen) * 2 - 1
+        dB = torch.rand((K, N), dtype=tdt, device="cuda:0", generator=gen) * 2 - 1
+        dC = torch.zeros((M, N), dtype=tdt, device="cuda:0")
+        flops = 2.0 * M * N * K
+        reps = max(5, min(300, int(1.5e12 / flops)))
+        times = {}
+        for v in (1, 2, 3, 4, 5):
+            def call():
+                gemm_ex(M, N, K, dA, K, dB, N, dC, N, stream=stream, variant=v)
+            t0 = time.perf_counter()
+            while time.perf_counter() - t0 < 0.2:
+                for _ in range(5):
+                    call()
+                torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                call()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            times[v] = e0.elapsed_time(e1) / reps
+        chosen = choose(M, N, K, cus)
+        best = min(times, key=times.get)
+        regret = times[chosen] / times[best] - 1.0
+        total += regret
+        rows.append({"shape": [M, N, K], "chosen": name(chosen), "chosen_ms": round(times[chosen], 5),
+                     "chosen_frac": round(flops / (times[chosen] * 1e-3) / 1e12 / peak, 4), "best": name(best),
+                     "best_ms": round(times[best], 5), "regret": round(regret, 4),
+                     "all_ms": {name(v): round(t, 5) for v, t in times.items()}})
+        log("%-18s chosen %-16s %9.4f ms (%5.1f %%) | best %-16s %9.4f ms | regret %4.1f %% | %s" % (
+            "%dx%dx%d" % (M, N, K), name(chosen), times[chosen], 100 * rows[-1]["chosen_frac"], name(best), times[best], 100 * regret,
+            " ".join("%s:%.4f" % (name(v).replace("mfma_", ""), t) for v, t in times.items())))
+    log("mean regret %.2f %%, largest %.2f %%" % (100 * total / len(rows), 100 * max(r["regret"] for r in rows)))
+    return {"dtype": "f32" if f32 else "f64", "mean_regret": round(total / len(rows), 4), "max_regret": max(r["regret"] for r in rows), "shapes": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -186,6 +242,8 @@ def main():
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the short timings of the configurations that are not the headline")
     ap.add_argument("--copy-calibration", action="store_true")
+    ap.add_argument("--selection-study", action="store_true",
+                    help="instead of the benchmark: time every tiled variant on 17 shapes and report the regret of the selection rule")
     ap.add_argument("--compare-vendor", action="store_true",
                     help="after the measurement, time the vendor BLAS behind torch.addmm on the same buffers (context only)")
     ap.add_argument("--cold-cache", action="store_true",
@@ -207,6 +265,10 @@ def main():
     binding.load()
     if args.copy_calibration:
         copy_calibration()
+        return
+    if args.selection_study:
+        print(json.dumps(selection_study(args.dtype == "f32", torch.cuda.current_stream(),
+                                         torch.cuda.get_device_properties(0).multi_processor_count)), flush=True)
         return
 
     import numpy as np

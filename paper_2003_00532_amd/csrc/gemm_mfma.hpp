@@ -23,6 +23,8 @@
 //   B operand: one element, (k = l / 16, j = l % 16)
 // and return four elements per lane, register r holding
 //   f64: (i = 4 * r + l / 16, j = l % 16)          f32: (i = 4 * (l / 16) + r, j = l % 16).
+// v_mfma_f32_32x32x2_f32 takes A (i = l % 32, k = l / 32), B (k = l / 32, j = l % 32) and returns sixteen elements per
+// lane, register r holding (i = 8 * (r / 4) + 4 * (l / 32) + r % 4, j = l % 32).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -34,34 +36,54 @@ namespace gemm_detail {
 typedef double v4d __attribute__((ext_vector_type(4)));
 typedef double v2d __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kXcds = 8;    // workgroups are dealt round-robin to 8 XCDs, each with a private L2
 constexpr int kGroupM = 8;  // tile rows per group of the grouped tile order
 constexpr int kThreads = 256;
 constexpr int kLean = 0, kGeneric = 1, kStaged = 2, kSampled = 3;  // kernel modes, see gemm_mfma_kernel
 
-// What depends on the element type.  A 16-byte LDS cell holds E consecutive k (for A) of one row;
-// one LDS stage is 8 cells deep, so BK = 8 * E (16 for double, 32 for float).
-template <typename T> struct Elem;
-template <> struct Elem<double> {
-    static constexpr int E = 2;
+// What depends on the element type and on the matrix instruction.  A 16-byte LDS cell holds E consecutive k (for A)
+// of one row; one LDS stage is 8 cells deep, so BK = 8 * E (16 for double, 32 for float).  The instruction works on
+// BLK x BLK blocks of C: lane l supplies one element of each operand, (x = l % BLK, k-lane kl = l / BLK), so one
+// instruction consumes KL = 64 / BLK values of k, and returns ACC elements of the block per lane, register r holding
+// row d_row(r, l), column l % BLK.  A half-stage is four cells deep; a lane reads cell KL * rr + kl of it for
+// rr = 0 .. RPH-1 (RPH = 4 / KL reads per block and half-stage) and each read feeds E instructions.
+//   double: v_mfma_f64_16x16x4_f64 (64 cycles), the only shape with full rate.
+//   float:  v_mfma_f32_16x16x4_f32 (32 cycles); v_mfma_f32_32x32x2_f32 (64 cycles: the instruction count and issue
+//           pattern per flop of the double kernel) is an option of the build that was measured and is not used, see
+//           gemm_mfma_kernel.
+template <typename T, int BLK> struct Elem;
+template <> struct Elem<double, 16> {
+    static constexpr int E = 2, BLK = 16, KL = 4, RPH = 1, ACC = 4;
     typedef v2d cell_t;
     typedef v4d acc_t;
     static __device__ __forceinline__ acc_t mfma(double a, double b, acc_t c)
     {
         return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
     }
-    static constexpr __device__ __forceinline__ int d_row(int r, int lg) { return 4 * r + lg; }
+    static constexpr __device__ __forceinline__ int d_row(int r, int kl) { return 4 * r + kl; }
 };
-template <> struct Elem<float> {
-    static constexpr int E = 4;
+template <> struct Elem<float, 16> {
+    static constexpr int E = 4, BLK = 16, KL = 4, RPH = 1, ACC = 4;
     typedef v4f cell_t;
     typedef v4f acc_t;
     static __device__ __forceinline__ acc_t mfma(float a, float b, acc_t c)
     {
         return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
     }
-    static constexpr __device__ __forceinline__ int d_row(int r, int lg) { return 4 * lg + r; }
+    static constexpr __device__ __forceinline__ int d_row(int r, int kl) { return 4 * kl + r; }
+};
+template <> struct Elem<float, 32> {
+    static constexpr int E = 4, BLK = 32, KL = 2, RPH = 2, ACC = 16;
+    typedef v4f cell_t;
+    typedef v16f acc_t;
+    static __device__ __forceinline__ acc_t mfma(float a, float b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+    }
+    // four groups of four consecutive rows, 8 rows apart; the two k-lanes interleave them
+    static constexpr __device__ __forceinline__ int d_row(int r, int kl) { return 8 * (r / 4) + 4 * kl + r % 4; }
 };
 
 // Split K: a launch of grid height S computes S consecutive slices of the k range, slice y into its own
@@ -288,7 +310,7 @@ __device__ __forceinline__ T scaled_update(T alpha, T s, T beta, T c, bool read_
 // the literal 1.
 template <typename T, bool KMAJOR, int BX, bool GENERIC>
 struct Panel {
-    typedef Elem<T> EL;
+    typedef Elem<T, 16> EL;   // the cell is the same for every instruction shape
     typedef typename EL::cell_t cell_t;
     static constexpr int E = EL::E;
     static constexpr int SZ = (int)sizeof(T);
@@ -426,26 +448,35 @@ struct Panel {
         }
     }
 
-    // byte offset, inside this panel's part of a stage, of the first fragment of the wave whose patch
-    // starts at element wx_off of the panel
+    // Byte offset, inside this panel's part of a stage, of the first fragment of the wave whose patch starts at
+    // element wx_off of the panel, for an instruction on BLK-wide blocks: lane l supplies x = l % BLK at k-lane
+    // kl = l / BLK (with BLK = 32 the two 16-row chunks of a block are addressed by bit 4 of the lane number).
+    template <int BLK>
     __device__ __forceinline__ int frag_base(int wx_off) const
     {
-        if constexpr (KMAJOR) return ((wx_off / 16) << 1) * 1024 + l * 16;      // + xi*2048 + h*1024
-        else return lg * GROUP + (wx_off + li) * SZ;                            // + h*4*GROUP + xi*16*SZ + e*ROW
+        const int xr = l % BLK, kl = l / BLK;
+        if constexpr (KMAJOR) return (((wx_off / 16) + (xr >> 4)) << 1) * 1024 + (kl * 16 + (xr & 15)) * 16;
+        else return kl * GROUP + (wx_off + xr) * SZ;
     }
 
-    // fragments of one half-stage (h) = E MFMA k-steps, for XI consecutive 16-wide blocks
-    template <int XI>
-    static __device__ __forceinline__ void read_frags(const char *panel, int fbase, int h, cell_t (&f)[XI])
+    // Fragments of one half-stage (h): for XI consecutive BLK-wide blocks, RPH reads each; read rr of a lane is cell
+    // KL * rr + kl of the half-stage, whose E elements feed E MFMA k-steps.
+    template <int XI, int BLK>
+    static __device__ __forceinline__ void read_frags(const char *panel, int fbase, int h, cell_t (&f)[XI * (BLK / 16)])
     {
+        constexpr int KL = 64 / BLK, RPH = 4 / KL;
+        static_assert(RPH == BLK / 16, "reads per block");
 #pragma unroll
         for (int xi = 0; xi < XI; ++xi) {
-            if constexpr (KMAJOR) {
-                f[xi] = *reinterpret_cast<const cell_t *>(panel + fbase + xi * 2048 + h * 1024);
-            } else {
-                const char *p = panel + fbase + h * 4 * GROUP + xi * 16 * SZ;
 #pragma unroll
-                for (int e = 0; e < E; ++e) f[xi][e] = *reinterpret_cast<const T *>(p + e * ROW);
+            for (int rr = 0; rr < RPH; ++rr) {
+                if constexpr (KMAJOR) {
+                    f[xi * RPH + rr] = *reinterpret_cast<const cell_t *>(panel + fbase + xi * (BLK / 16) * 2048 + h * 1024 + rr * KL * 256);
+                } else {
+                    const char *p = panel + fbase + h * 4 * GROUP + rr * KL * GROUP + xi * BLK * SZ;
+#pragma unroll
+                    for (int e = 0; e < E; ++e) f[xi * RPH + rr][e] = *reinterpret_cast<const T *>(p + e * ROW);
+                }
             }
         }
     }
@@ -490,10 +521,20 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha_, const T *__restrict__ A_, 
     const T *__restrict__ A = A_ + slice * (tail_unit ? tail.step_a : split.step_a);
     const T *__restrict__ B = B_ + slice * (tail_unit ? tail.step_b : split.step_b);
     const T alpha = tail_unit ? T(1) : alpha_, beta = tail_unit ? T(0) : beta_;
-    typedef Elem<T> EL;
+    constexpr int TM = BM / WM, TN = BN / WN;
+    // Single precision can also run on 32 x 32 blocks (-DGEMM_F32_WIDE_BLOCKS).  Measured on MI355X it is correct (the
+    // whole float test-suite passes) and never faster: 8192^3 93.6 against 95.5 % of peak with the 128 x 128 tile, 93.0
+    // against 96.2 % with 64 x 128, the same at 2048^3, with the same LDS instruction count, no bank conflicts and the
+    // same matrix-pipe cycles in the counters; so the 16 x 16 instruction is what the library builds.
+#ifdef GEMM_F32_WIDE_BLOCKS
+    constexpr int BLK = (std::is_same<T, float>::value && TM % 32 == 0 && TN % 32 == 0) ? 32 : 16;
+#else
+    constexpr int BLK = 16;
+#endif
+    typedef Elem<T, BLK> EL;
     typedef typename EL::cell_t cell_t;
     typedef typename EL::acc_t acc_t;
-    constexpr int E = EL::E;
+    constexpr int E = EL::E, RPH = EL::RPH;
     constexpr int SZ = (int)sizeof(T);
     static_assert(E * SZ == 16, "a cell is 16 bytes");
     constexpr int BK = 8 * E;
@@ -502,9 +543,8 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha_, const T *__restrict__ A_, 
     constexpr bool SAMPLED = MODE == kSampled;
     static_assert(MODE == kLean || MODE == kGeneric || MODE == kStaged || MODE == kSampled, "kernel mode");
     static_assert(WM * WN == 4, "four waves per workgroup");
-    constexpr int TM = BM / WM, TN = BN / WN;
-    constexpr int MI = TM / 16, NI = TN / 16;
-    static_assert(MI >= 1 && NI >= 1 && TM % 16 == 0 && TN % 16 == 0, "wave tile is a grid of 16x16 tiles");
+    constexpr int MI = TM / BLK, NI = TN / BLK;
+    static_assert(MI >= 1 && NI >= 1 && TM % BLK == 0 && TN % BLK == 0, "wave tile is a grid of BLK x BLK blocks");
     typedef Panel<T, !TA, BM, GENERIC> PA;
     typedef Panel<T, TB, BN, GENERIC> PB;
     constexpr int A_STAGE = PA::STAGE_BYTES;
@@ -517,7 +557,7 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha_, const T *__restrict__ A_, 
     const int w = __builtin_amdgcn_readfirstlane(t >> 6);
     const int l = t & 63;
     const int wm = w / WN, wn = w % WN;
-    const int lg = l >> 4, li = l & 15;
+    const int kl = l / BLK, lx = l % BLK;   // this lane's k-lane and its column inside a block of C
 
     uint32_t tm_u, tn_u;
     tile_at(tail_unit ? tail.begin + unit_tile : position_of_block(blockIdx.x, map), map, tm_u, tn_u);
@@ -565,32 +605,35 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha_, const T *__restrict__ A_, 
     };
 
     // ---- operand fragments: one half-stage (h) = E MFMA k-steps -------------------------------
-    const int a_frag = pa.frag_base(wm * TM);
-    const int b_frag = A_STAGE + pb.frag_base(wn * TN);
-    auto read_frags = [&](int buf, int h, cell_t (&fa)[MI], cell_t (&fb)[NI]) {
+    const int a_frag = pa.template frag_base<BLK>(wm * TM);
+    const int b_frag = A_STAGE + pb.template frag_base<BLK>(wn * TN);
+    auto read_frags = [&](int buf, int h, cell_t (&fa)[MI * RPH], cell_t (&fb)[NI * RPH]) {
         const char *stage = lds + buf * STAGE;
-        PA::template read_frags<MI>(stage, a_frag, h, fa);
-        PB::template read_frags<NI>(stage, b_frag, h, fb);
+        PA::template read_frags<MI, BLK>(stage, a_frag, h, fa);
+        PB::template read_frags<NI, BLK>(stage, b_frag, h, fb);
     };
 
     acc_t acc[MI][NI];
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = acc_t{T(0), T(0), T(0), T(0)};
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int r = 0; r < EL::ACC; ++r) acc[mi][ni][r] = T(0);
 
-    // MFMAs lo .. hi-1 of the E * MI * NI that consume one half-stage, in the order e, mi, ni
-    constexpr int HALF = E * MI * NI;
-    auto mfma_range = [&](const cell_t (&fa)[MI], const cell_t (&fb)[NI], int lo, int hi) {
+    // MFMAs lo .. hi-1 of the RPH * E * MI * NI that consume one half-stage, in the order read, e, mi, ni (the
+    // first ones only need the first read of every block)
+    constexpr int HALF = RPH * E * MI * NI;
+    auto mfma_range = [&](const cell_t (&fa)[MI * RPH], const cell_t (&fb)[NI * RPH], int lo, int hi) {
 #pragma unroll
         for (int idx = 0; idx < HALF; ++idx) {
             if (idx < lo || idx >= hi) continue;
-            const int e = idx / (MI * NI), mi = (idx / NI) % MI, ni = idx % NI;
-            acc[mi][ni] = EL::mfma(fa[mi][e], fb[ni][e], acc[mi][ni]);
+            const int rr = idx / (E * MI * NI), e = (idx / (MI * NI)) % E, mi = (idx / NI) % MI, ni = idx % NI;
+            acc[mi][ni] = EL::mfma(fa[mi * RPH + rr][e], fb[ni * RPH + rr][e], acc[mi][ni]);
         }
     };
 
-    cell_t fa0[MI], fb0[NI], fa1[MI], fb1[NI];
+    cell_t fa0[MI * RPH], fb0[NI * RPH], fa1[MI * RPH], fb1[NI * RPH];
 
     // prologue: stages 0 and 1
     for (int kt = 0; kt < 2 && kt < nk; ++kt) {
@@ -659,87 +702,76 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha_, const T *__restrict__ A_, 
     // as the loops go (a 64-bit add per row instead of a multiply per element); columns of one row are
     // a compile-time offset apart.
     auto write_tile = [&]() {
-        const int row_base = m0 + wm * TM + EL::d_row(0, lg);
-        const int col_base = n0 + wn * TN + li;
+        // Result register r = 4 g + q of a block holds row d_row(r, kl): groups g of four registers ROW_STEP rows
+        // apart, the groups GROUP_STEP rows apart (one group for the 16 x 16 instructions, four for 32 x 32).
+        constexpr int ACC = EL::ACC, GROUPS = ACC / 4;
         constexpr int ROW_STEP = EL::d_row(1, 0) - EL::d_row(0, 0);   // 4 for double, 1 for float
+        constexpr int GROUP_STEP = GROUPS > 1 ? EL::d_row(4 % ACC, 0) - EL::d_row(0, 0) : 0;
         static_assert(EL::d_row(2, 0) - EL::d_row(1, 0) == ROW_STEP && EL::d_row(3, 0) - EL::d_row(2, 0) == ROW_STEP, "");
-        constexpr int MB = (MI >= 2) ? 2 : 1;
+        static_assert(GROUPS == 1 || EL::d_row(ACC - 4, 0) - EL::d_row(0, 0) == (GROUPS - 1) * GROUP_STEP, "");
+        const int row_base = m0 + wm * TM + EL::d_row(0, kl);
+        const int col_base = n0 + wn * TN + lx;
+        constexpr int MB = (ACC == 4 && MI >= 2) ? 2 : 1;   // blocks of rows whose loads are in flight together
         const int64_t cs_c = SAMPLED ? es.c : 1;   // elements between neighbouring columns of C
         T *const c_lane = C + (int64_t)row_base * ldc + col_base * cs_c;
-        const int64_t r_step = (int64_t)ROW_STEP * ldc, mi_step = 16 * ldc;
+        const int64_t r_step = (int64_t)ROW_STEP * ldc, g_step = (int64_t)GROUP_STEP * ldc, mi_step = (int64_t)BLK * ldc;
         // Four forms, chosen once per workgroup: alpha = beta = 1 (the paper's own operation: one addition
         // per element) with the addition done by the lane or, on request of the host, by the memory system
         // (no-return floating-point atomics: each element belongs to one lane, so it is the same single rounding);
         // beta = 0 (C is not read); and the general one.
         constexpr int kUnit = 0, kOverwrite = 1, kScaled = 2, kUnitAtomic = 3;
+        // visits every element (mi, ni, r) of the blocks mb .. mb + MB - 1 with its address and whether it exists
+        auto for_each = [&](int mb, T *c_mb, auto &&body) {
+            T *c_mi = c_mb;
+#pragma unroll
+            for (int mi = mb; mi < mb + MB; ++mi) {
+#pragma unroll
+                for (int g = 0; g < GROUPS; ++g) {
+                    T *c_r = c_mi + g * g_step;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int r = 4 * g + q;
+                        const int row = row_base + mi * BLK + g * GROUP_STEP + q * ROW_STEP;
+#pragma unroll
+                        for (int ni = 0; ni < NI; ++ni) {
+                            const int col = col_base + ni * BLK;
+                            body(mi, ni, r, &c_r[ni * BLK * cs_c], !GENERIC || tile_full || (row < M && col < N));
+                        }
+                        c_r += r_step;
+                    }
+                }
+                c_mi += mi_step;
+            }
+        };
         auto epilogue = [&](auto kind_tag) {
             constexpr int KIND = decltype(kind_tag)::value;
             constexpr bool UNIT = KIND == kUnit;
             constexpr bool read_c = KIND != kOverwrite;
             T *c_mb = c_lane;
-            if constexpr (KIND == kUnitAtomic) {
-    #pragma unroll
-                for (int mi = 0; mi < MI; ++mi) {
-                    T *c_r = c_mb;
-    #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int row = row_base + mi * 16 + r * ROW_STEP;
-    #pragma unroll
-                        for (int ni = 0; ni < NI; ++ni) {
-                            const int col = col_base + ni * 16;
-                            if (!GENERIC || tile_full || (row < M && col < N)) unsafeAtomicAdd(&c_r[ni * 16 * cs_c], acc[mi][ni][r]);
-                        }
-                        c_r += r_step;
-                    }
-                    c_mb += mi_step;
-                }
-                return;
-            }
-    #pragma unroll
+#pragma unroll
             for (int mb = 0; mb < MI; mb += MB) {
-                T cin[MB][NI][4];
-                T *c_mi = c_mb;
-    #pragma unroll
-                for (int mi = mb; mi < mb + MB; ++mi) {
-                    T *c_r = c_mi;
-    #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int row = row_base + mi * 16 + r * ROW_STEP;
-    #pragma unroll
-                        for (int ni = 0; ni < NI; ++ni) {
-                            const int col = col_base + ni * 16;
-                            if (read_c && (!GENERIC || tile_full || (row < M && col < N))) cin[mi - mb][ni][r] = c_r[ni * 16 * cs_c];
-                            else cin[mi - mb][ni][r] = T(0);
-                        }
-                        c_r += r_step;
-                    }
-                    c_mi += mi_step;
-                }
-                c_mi = c_mb;
-    #pragma unroll
-                for (int mi = mb; mi < mb + MB; ++mi) {
-                    T *c_r = c_mi;
-    #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int row = row_base + mi * 16 + r * ROW_STEP;
-    #pragma unroll
-                        for (int ni = 0; ni < NI; ++ni) {
-                            const int col = col_base + ni * 16;
-                            if (!GENERIC || tile_full || (row < M && col < N))
-                                c_r[ni * 16 * cs_c] = UNIT ? cin[mi - mb][ni][r] + acc[mi][ni][r]
-                                                    : scaled_update(alpha, acc[mi][ni][r], beta, cin[mi - mb][ni][r], read_c);
-                        }
-                        c_r += r_step;
-                    }
-                    c_mi += mi_step;
+                if constexpr (KIND == kUnitAtomic) {
+                    for_each(mb, c_mb, [&](int mi, int ni, int r, T *c, bool live) {
+                        if (live) unsafeAtomicAdd(c, acc[mi][ni][r]);
+                    });
+                } else {
+                    T cin[MB][NI][ACC];
+                    for_each(mb, c_mb, [&](int mi, int ni, int r, T *c, bool live) {
+                        cin[mi - mb][ni][r] = (read_c && live) ? *c : T(0);
+                    });
+                    for_each(mb, c_mb, [&](int mi, int ni, int r, T *c, bool live) {
+                        if (live)
+                            *c = UNIT ? cin[mi - mb][ni][r] + acc[mi][ni][r]
+                                      : scaled_update(alpha, acc[mi][ni][r], beta, cin[mi - mb][ni][r], read_c);
+                    });
                 }
                 c_mb += MB * mi_step;
             }
-    };
-    if (alpha == T(1) && beta == T(1) && (split.flags & kFlagAtomicC)) epilogue(std::integral_constant<int, kUnitAtomic>{});
-    else if (alpha == T(1) && beta == T(1)) epilogue(std::integral_constant<int, kUnit>{});
-    else if (beta == T(0)) epilogue(std::integral_constant<int, kOverwrite>{});
-    else epilogue(std::integral_constant<int, kScaled>{});
+        };
+        if (alpha == T(1) && beta == T(1) && (split.flags & kFlagAtomicC)) epilogue(std::integral_constant<int, kUnitAtomic>{});
+        else if (alpha == T(1) && beta == T(1)) epilogue(std::integral_constant<int, kUnit>{});
+        else if (beta == T(0)) epilogue(std::integral_constant<int, kOverwrite>{});
+        else epilogue(std::integral_constant<int, kScaled>{});
     };
 
     int s = 0;

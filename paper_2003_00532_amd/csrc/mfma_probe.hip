@@ -27,7 +27,7 @@ constexpr int kProbeWorkgroupsPerCu = 2;
 template <typename T>
 __global__ void __launch_bounds__(kThreads, 2) mfma_probe_kernel(int64_t iterations, T *__restrict__ sink)
 {
-    typedef Elem<T> EL;
+    typedef Elem<T, 16> EL;
     typedef typename EL::acc_t acc_t;
     // operands small enough that the sums stay far from overflow for any iteration count in range
     const T a = T(1) / T(1 << 20) * T(1 + (threadIdx.x & 3)), b = T(1) / T(1 << 20);
