@@ -512,15 +512,37 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha_, const T *__restrict__ A_, 
     // What this workgroup computes: a whole tile (of slice blockIdx.y of k when the grid has a height), or, past
     // tail.begin, one k slice of one of the last tiles into its own slab (see TailSplit).  Everything here is
     // wave-uniform and stays on the scalar unit.
+    // Every kernel argument the prologue needs is requested here, in one batch of scalar loads with one wait; left to
+    // itself the compiler fetches them one dependent group after the other along the branches below.
+    asm volatile("" ::"s"(A_), "s"(B_), "s"(C_), "s"(lda), "s"(ldb), "s"(ldc_), "s"(map.per), "s"(map.rem), "s"(map.width.magic),
+                 "s"(map.width.shift), "s"(map.width.d), "s"(map.tiles_m), "s"(map.last.magic), "s"(map.last.shift), "s"(map.last.d),
+                 "s"(split.k_chunk), "s"(tail.begin), "s"(K_total), "s"(M), "s"(N));
     const bool tail_unit = blockIdx.x >= tail.begin;
-    const uint32_t unit = tail_unit ? blockIdx.x - tail.begin : 0u;
-    const uint32_t unit_tile = fast_div(unit, tail.splits);
-    const int slice = tail_unit ? (int)(unit - unit_tile * tail.splits.d) : (int)blockIdx.y;
-    const int k_chunk = tail_unit ? tail.k_chunk : split.k_chunk;
+    uint32_t position;          // of the tile in the grouped order
+    int slice, k_chunk;
+    int64_t step_a, step_b;
+    uint32_t unit = 0;
+    T alpha = alpha_, beta = beta_;
+    if (!tail_unit) {
+        position = position_of_block(blockIdx.x, map);
+        slice = (int)blockIdx.y;
+        k_chunk = split.k_chunk;
+        step_a = split.step_a;
+        step_b = split.step_b;
+    } else {
+        unit = blockIdx.x - tail.begin;
+        const uint32_t unit_tile = fast_div(unit, tail.splits);
+        position = tail.begin + unit_tile;
+        slice = (int)(unit - unit_tile * tail.splits.d);
+        k_chunk = tail.k_chunk;
+        step_a = tail.step_a;
+        step_b = tail.step_b;
+        alpha = T(1);
+        beta = T(0);
+    }
     const int K = min(k_chunk, K_total - slice * k_chunk);
-    const T *__restrict__ A = A_ + slice * (tail_unit ? tail.step_a : split.step_a);
-    const T *__restrict__ B = B_ + slice * (tail_unit ? tail.step_b : split.step_b);
-    const T alpha = tail_unit ? T(1) : alpha_, beta = tail_unit ? T(0) : beta_;
+    const T *__restrict__ A = A_ + slice * step_a;
+    const T *__restrict__ B = B_ + slice * step_b;
     constexpr int TM = BM / WM, TN = BN / WN;
     // Single precision can also run on 32 x 32 blocks (-DGEMM_F32_WIDE_BLOCKS).  Measured on MI355X it is correct (the
     // whole float test-suite passes) and never faster: 8192^3 93.6 against 95.5 % of peak with the 128 x 128 tile, 93.0
@@ -560,7 +582,7 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha_, const T *__restrict__ A_, 
     const int kl = l / BLK, lx = l % BLK;   // this lane's k-lane and its column inside a block of C
 
     uint32_t tm_u, tn_u;
-    tile_at(tail_unit ? tail.begin + unit_tile : position_of_block(blockIdx.x, map), map, tm_u, tn_u);
+    tile_at(position, map, tm_u, tn_u);
     const int m0 = (int)tm_u * BM, n0 = (int)tn_u * BN;
     // the output: C itself, or the slab of this unit addressed as if it were the tile's place in a matrix of BN columns
     const int64_t ldc = tail_unit ? (int64_t)BN : ldc_;
