@@ -168,6 +168,27 @@ def other_workloads(gemm_ex, choose, variant_name, np_dtype, peak, seed, stream,
                      "tflops": round(w.flops / (ms * 1e-3) / 1e12, 3), "frac": round(w.flops / (ms * 1e-3) / 1e12 / peak, 4),
                      "back_to_back_ms": round(b2b, 5), "back_to_back_tflops": round(w.flops / (b2b * 1e-3) / 1e12, 3),
                      "back_to_back_frac": round(w.flops / (b2b * 1e-3) / 1e12 / peak, 4)}
+        # the same workload through the entry point that takes a workspace, when its plan would use one
+        from paper_2003_00532_amd import binding as _b
+        f32w = np_dtype == np.float32
+        ws_bytes = (_b.gemm_f32_split_k_workspace_bytes if f32w else _b.gemm_f64_split_k_workspace_bytes)(0, 0, w.M, w.N, w.K, cus)
+        if ws_bytes > 0:
+            general_ws = _b.gemm_f32_general_ws if f32w else _b.gemm_f64_general_ws
+            workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dA.device)
+
+            def call_ws():
+                general_ws(0, 0, w.M, w.N, w.K, 1.0, dA, w.lda, dB, w.ldb, 1.0, dC, w.ldc, workspace, ws_bytes, stream=stream)
+
+            for _ in range(10):
+                call_ws()
+            sep_ws, b2b_ws = time_launches(call_ws, stream, launches)
+            tplan = (_b.gemm_f32_tail_split_plan if f32w else _b.gemm_f64_tail_split_plan)(0, 0, w.M, w.N, w.K, cus)
+            out[name]["with_workspace"] = {
+                "entry_point": "general_ws, alpha = beta = 1", "workspace_bytes": ws_bytes, "kernel_variant": variant_name(tplan[0]),
+                "tail_split": {"tiles": tplan[1], "slices": tplan[2], "k_chunk": tplan[3]},
+                "ms": round(sum(sep_ws) / len(sep_ws), 5), "frac": round(w.flops / (sum(sep_ws) / len(sep_ws) * 1e-3) / 1e12 / peak, 4),
+                "back_to_back_ms": round(b2b_ws, 5), "back_to_back_frac": round(w.flops / (b2b_ws * 1e-3) / 1e12 / peak, 4)}
+            del workspace
         log("%s: %s" % (name, json.dumps(out[name])))
         del dA, dB, dC
     return out
@@ -241,6 +262,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the short timings of the configurations that are not the headline")
+    ap.add_argument("--with-workspace", action="store_true",
+                    help="time gemm_*_general_ws (alpha = beta = 1) with the workspace its plan asks for instead of gemm_*_ex: "
+                         "the k range, or the k range of the last tiles only, may then be split")
     ap.add_argument("--copy-calibration", action="store_true")
     ap.add_argument("--selection-study", action="store_true",
                     help="instead of the benchmark: time every tiled variant on 17 shapes and report the regret of the selection rule")
@@ -293,8 +317,24 @@ def main():
 
     stream = torch.cuda.current_stream()
 
+    ws_plan = None
+    if args.with_workspace:
+        general_ws = binding.gemm_f32_general_ws if f32 else binding.gemm_f64_general_ws
+        cus = props.multi_processor_count
+        ws_bytes = (binding.gemm_f32_split_k_workspace_bytes if f32 else binding.gemm_f64_split_k_workspace_bytes)(0, 0, w.M, w.N, w.K, cus)
+        workspace = torch.empty(max(1, ws_bytes), dtype=torch.uint8, device=dev)
+        sv, splits, chunk = (binding.gemm_f32_split_k_plan if f32 else binding.gemm_f64_split_k_plan)(0, 0, w.M, w.N, w.K, cus)
+        tv, ttiles, tsplits, tchunk = (binding.gemm_f32_tail_split_plan if f32 else binding.gemm_f64_tail_split_plan)(0, 0, w.M, w.N, w.K, cus)
+        variant = tv
+        vname = variant_name(variant)
+        ws_plan = {"workspace_bytes": ws_bytes, "split_k": {"slices": splits, "k_chunk": chunk},
+                   "tail_split": {"tiles": ttiles, "slices": tsplits, "k_chunk": tchunk}}
+
     def step():
-        gemm_ex(w.M, w.N, w.K, dA, w.lda, dB, w.ldb, dC, w.ldc, stream=stream, variant=args.variant)
+        if args.with_workspace:
+            general_ws(0, 0, w.M, w.N, w.K, 1.0, dA, w.lda, dB, w.ldb, 1.0, dC, w.ldc, workspace, ws_bytes, stream=stream)
+        else:
+            gemm_ex(w.M, w.N, w.K, dA, w.lda, dB, w.ldb, dC, w.ldc, stream=stream, variant=args.variant)
 
     for _ in range(args.warmup):
         step()
@@ -364,6 +404,9 @@ def main():
                      "back_to_back_frac": round(w.flops / (back_to_back_ms * 1e-3) / 1e12 / peak, 4),
                      "algorithmic_flops_per_launch": w.flops, "algorithmic_bytes_per_launch": alg_bytes},
     }
+    if ws_plan is not None:
+        out["config"]["entry_point"] = "gemm_%s_general_ws(0, 0, ..., alpha = 1, ..., beta = 1, ..., workspace)" % args.dtype
+        out["config"]["workspace_plan"] = ws_plan
     # The peak recomputed from what the device reports (compute units x 4 SIMDs x flops per MFMA / issue cycles x clock)
     cus, clock_khz, peak64, peak32 = binding.gemm_f64_device_peak()
     out["roofline"]["peak_from_device_props"] = round(peak32 if f32 else peak64, 2)

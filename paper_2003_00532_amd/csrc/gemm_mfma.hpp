@@ -102,8 +102,10 @@ struct ElemStrides {
     int64_t a, b, c;
 };
 
-// Optional phase trace (diagnostic builds only, -DGEMM_PHASE_TRACE): thread 0 of every workgroup stores the constant
-// 100 MHz clock at a few points of its life, and where it ran, into 8 slots of a buffer the host has installed.
+// Optional phase trace (diagnostic builds only, -DGEMM_PHASE_TRACE; driven by paper_2003_00532_amd/phase_trace.py):
+// wave 0 of every workgroup stores the constant 100 MHz clock at a few points of its life (slots 0, 3, 4, 5: entry,
+// after the first stage barrier, after the K loop, exit), the shader clock at entry and exit (slots 1, 2) and where
+// it ran (slot 7), into 8 slots of a buffer the host has installed.
 #ifdef GEMM_PHASE_TRACE
 static __device__ unsigned long long *g_phase_trace;
 #define GEMM_PHASE_MARK(i)                                                                                      \
