@@ -99,3 +99,48 @@ def test_automatic_choice_and_host_memory(gpu_device, epilogue_mode):
     epilogue_mode(0)
     with pytest.raises(binding.GemmF64Error):
         binding.gemm_f64_set_epilogue_mode(7)
+
+
+def test_in_memory_form_under_graph_capture(gpu_device, epilogue_mode):
+    # the automatic rule asks the runtime who owns C; that query, and the additions in memory, must work in a captured
+    # stream and on every replay
+    M = N = 1024
+    K = 256
+    Ab, Bb, Cb = (synth.matrix(6, t, r, c, None, "int")[0] for t, r, c in ((synth.TAG_A, M, K), (synth.TAG_B, K, N), (synth.TAG_C, M, N)))
+    want = Cb.copy()
+    oracle.gemm_f64_ref(Ab, Bb, want)
+    dA, dB, c_init = gpu_util.to_dev(Ab), gpu_util.to_dev(Bb), gpu_util.to_dev(Cb)
+    out = torch.empty_like(c_init)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            out.copy_(c_init)
+            binding.gemm_f64(M, N, K, dA, K, dB, N, out, N, stream=side)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        pins.assert_bitwise(out.cpu().numpy(), want, "graph replay %d" % rep)
+        _ = (dA[:8, :8] @ dB[:8, :8]).sum().item()
+
+
+def test_products_below_the_normal_range(gpu_device):
+    # Sums of products that are themselves subnormal (operands around 2^-540): the CPU definition keeps them as
+    # subnormal numbers; the matrix unit is allowed to return them as they are or as signed zeros (it flushes them on
+    # MI355X).  Either way nothing else may change, and sums in the normal range next to them are unaffected.
+    M, N, K = 64, 64, 32
+    rng = np.random.default_rng(8)
+    A = rng.uniform(0.5, 1.0, (M, K)); B = rng.uniform(0.5, 1.0, (K, N)); C0 = np.zeros((M, N))
+    A[:32] *= 2.0 ** -540; B[:, :32] *= 2.0 ** -540       # top-left quadrant: sums around 2^-1076
+    _, _, got = gpu_util.run_device(A, B, C0.copy(), M, N, K)
+    want = C0.copy(); oracle.gemm_f64_ref(A, B, want)
+    tiny = got[:32, :32]
+    flushed = bool(np.all(tiny == 0))
+    kept = bool(np.all(np.abs(tiny - want[:32, :32]) <= 2.0 ** -1074 * K))
+    print("subnormal products: %s" % ("flushed to zero" if flushed else "kept" if kept else "mixed"))
+    assert flushed or kept
+    S = np.zeros((M, N)); oracle.gemm_f64_absref(A, B, S)
+    rest = np.ones((M, N), bool); rest[:32, :32] = False
+    assert np.all(np.abs(got - want)[rest] <= 1e-13 * S[rest])
