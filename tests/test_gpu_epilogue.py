@@ -144,3 +144,35 @@ def test_products_below_the_normal_range(gpu_device):
     S = np.zeros((M, N)); oracle.gemm_f64_absref(A, B, S)
     rest = np.ones((M, N), bool); rest[:32, :32] = False
     assert np.all(np.abs(got - want)[rest] <= 1e-13 * S[rest])
+
+
+def test_fine_grained_device_memory(gpu_device, epilogue_mode):
+    # C in device memory allocated fine-grained (coherent with the host at a finer grain): still device memory to the
+    # runtime's query, and the additions in memory are performed there as in ordinary device memory
+    import ctypes
+    try:
+        hip = ctypes.CDLL("libamdhip64.so")
+        alloc, free, copy = hip.hipExtMallocWithFlags, hip.hipFree, hip.hipMemcpy
+    except (OSError, AttributeError):
+        pytest.skip("HIP runtime entry points not reachable through ctypes")
+    M = N = 1024
+    K = 256
+    Ab, Bb, Cb = (synth.matrix(7, t, r, c, None, "int")[0] for t, r, c in ((synth.TAG_A, M, K), (synth.TAG_B, K, N), (synth.TAG_C, M, N)))
+    want = Cb.copy()
+    oracle.gemm_f64_ref(Ab, Bb, want)
+    dA, dB = gpu_util.to_dev(Ab), gpu_util.to_dev(Bb)
+    p = ctypes.c_void_p()
+    if alloc(ctypes.byref(p), ctypes.c_size_t(M * N * 8), ctypes.c_uint(1)) != 0 or not p.value:   # hipDeviceMallocFinegrained
+        pytest.skip("fine-grained device memory not available")
+    try:
+        for mode in (0, IN_MEMORY, LOAD_STORE):
+            assert copy(p, ctypes.c_void_p(Cb.ctypes.data), ctypes.c_size_t(M * N * 8), 1) == 0
+            epilogue_mode(mode)
+            binding.gemm_f64(M, N, K, dA, K, dB, N, p.value, N)
+            torch.cuda.synchronize()
+            out = np.empty((M, N))
+            assert copy(ctypes.c_void_p(out.ctypes.data), p, ctypes.c_size_t(M * N * 8), 2) == 0
+            pins.assert_bitwise(out, want, "fine-grained C, mode %d" % mode)
+    finally:
+        epilogue_mode(0)
+        free(p)
