@@ -170,6 +170,7 @@ def other_workloads(gemm_ex, choose, variant_name, np_dtype, peak, seed, stream,
                      "back_to_back_frac": round(w.flops / (b2b * 1e-3) / 1e12 / peak, 4)}
         # the same workload through the entry point that takes a workspace, when its plan would use one
         from paper_2003_00532_amd import binding as _b
+        import numpy as np
         f32w = np_dtype == np.float32
         ws_bytes = (_b.gemm_f32_split_k_workspace_bytes if f32w else _b.gemm_f64_split_k_workspace_bytes)(0, 0, w.M, w.N, w.K, cus)
         if ws_bytes > 0:
