@@ -637,23 +637,29 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha_, const T *__restrict__ A_, 
         PB::template read_frags<NI, BLK>(stage, b_frag, h, fb);
     };
 
+    // The accumulators are not cleared: the first MFMA into each of them (the first MI * NI of a tile's first
+    // half-stage) takes a zero third operand instead, which the instruction accepts as a constant.  Clearing 64 to 128
+    // registers per lane with moves costs a workgroup that starts under load one to three microseconds, because every
+    // vector instruction of a young wave queues behind the matrix instructions of the older ones.
     acc_t acc[MI][NI];
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-            for (int r = 0; r < EL::ACC; ++r) acc[mi][ni][r] = T(0);
 
     // MFMAs lo .. hi-1 of the RPH * E * MI * NI that consume one half-stage, in the order read, e, mi, ni (the
     // first ones only need the first read of every block)
     constexpr int HALF = RPH * E * MI * NI;
-    auto mfma_range = [&](const cell_t (&fa)[MI * RPH], const cell_t (&fb)[NI * RPH], int lo, int hi) {
+    auto mfma_range = [&](const cell_t (&fa)[MI * RPH], const cell_t (&fb)[NI * RPH], int lo, int hi, auto fresh_tag) {
+        constexpr bool FRESH = decltype(fresh_tag)::value;   // the accumulators hold nothing yet
 #pragma unroll
         for (int idx = 0; idx < HALF; ++idx) {
             if (idx < lo || idx >= hi) continue;
             const int rr = idx / (E * MI * NI), e = (idx / (MI * NI)) % E, mi = (idx / NI) % MI, ni = idx % NI;
-            acc[mi][ni] = EL::mfma(fa[mi * RPH + rr][e], fb[ni * RPH + rr][e], acc[mi][ni]);
+            if (FRESH && idx < MI * NI) {
+                acc_t zero;
+#pragma unroll
+                for (int r = 0; r < EL::ACC; ++r) zero[r] = T(0);
+                acc[mi][ni] = EL::mfma(fa[mi * RPH + rr][e], fb[ni * RPH + rr][e], zero);
+            } else {
+                acc[mi][ni] = EL::mfma(fa[mi * RPH + rr][e], fb[ni * RPH + rr][e], acc[mi][ni]);
+            }
         }
     };
 
@@ -681,16 +687,16 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha_, const T *__restrict__ A_, 
     // barrier together while the other workgroup fills the gaps: +0.5 % at 8192^3.  With three or four waves
     // per SIMD the same scheme costs 2 to 5 %, so the smaller tiles leave priorities alone.
     constexpr bool RUSH_TO_BARRIER = BM * BN >= 128 * 128;
-    auto iteration = [&](int s, auto cur_tag) {
+    auto iteration = [&](int s, auto cur_tag, auto fresh_tag) {
         constexpr int cur = decltype(cur_tag)::value;
         // The first MFMAs wait for fragments that were requested long ago; only then are the next
         // reads queued, so that wait never covers a read that has just been issued.
         if constexpr (RUSH_TO_BARRIER) __builtin_amdgcn_s_setprio(1);
-        mfma_range(fa0, fb0, 0, NI);
+        mfma_range(fa0, fb0, 0, NI, fresh_tag);
         __builtin_amdgcn_sched_barrier(0);
         read_frags(cur, 1, fa1, fb1);
         __builtin_amdgcn_sched_barrier(0);
-        mfma_range(fa0, fb0, NI, HALF);
+        mfma_range(fa0, fb0, NI, HALF, fresh_tag);
         if constexpr (STAGED) {
             if (s >= 1 && s + 1 < nk) {  // stage s + 1 was loaded during the previous iteration
                 pa.store_regs(lds + (cur ^ 1) * STAGE, reinterpret_cast<const T(&)[E * NA]>(sa));
@@ -714,7 +720,7 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha_, const T *__restrict__ A_, 
             fetch_early(s + 2, cur);
         }
         __builtin_amdgcn_sched_barrier(0);
-        mfma_range(fa1, fb1, 0, HALF);
+        mfma_range(fa1, fb1, 0, HALF, std::false_type{});
     };
     // C <- alpha * (A B) + beta * C, C read (unless beta is zero: then it may hold anything, NaN
     // included) and written exactly once per element, after the K loop.  With alpha = beta = 1 the
@@ -798,12 +804,15 @@ gemm_mfma_kernel(int M, int N, int K_total, T alpha_, const T *__restrict__ A_, 
         else epilogue(std::integral_constant<int, kScaled>{});
     };
 
-    int s = 0;
+    // the first iteration is the one that meets fresh accumulators (nk >= 1: the host launches nothing for K == 0)
+    iteration(0, std::integral_constant<int, 0>{}, std::true_type{});
+    if (nk > 1) iteration(1, std::integral_constant<int, 1>{}, std::false_type{});
+    int s = 2;
     for (; s + 1 < nk; s += 2) {
-        iteration(s, std::integral_constant<int, 0>{});
-        iteration(s + 1, std::integral_constant<int, 1>{});
+        iteration(s, std::integral_constant<int, 0>{}, std::false_type{});
+        iteration(s + 1, std::integral_constant<int, 1>{}, std::false_type{});
     }
-    if (s < nk) iteration(s, std::integral_constant<int, 0>{});
+    if (s < nk) iteration(s, std::integral_constant<int, 0>{}, std::false_type{});
     GEMM_PHASE_MARK(4);
     write_tile();
     GEMM_PHASE_MARK(5);

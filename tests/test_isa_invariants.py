@@ -78,14 +78,22 @@ def test_k_loop_touches_no_c_and_has_no_vector_alu_work(asm):
         if mode != 0:
             continue  # the lean instantiation is the steady-state loop; the others add the zero-filled VGPR path
         blocks = mfma_blocks(k["body"])
-        assert blocks, name
+        assert len(blocks) > 2, name
         ops = collections.Counter(op for b in blocks for op in b)
         assert not any(op.startswith(("global_load_dword", "global_store", "buffer_", "flat_", "scratch_")) for op in ops), \
             "%s: the MFMA blocks access memory other than through global->LDS copies: %s" % (name, dict(ops))
+        # The first two blocks are the peeled first iteration of a tile (its MFMAs take a zero accumulator operand and the
+        # LDS addresses are set up among them); the steady-state loop and the last iteration follow and hold next to no
+        # vector-ALU instruction (the few that remain are address increments of LDS reads whose offsets exceed the
+        # immediate field).
+        first = collections.Counter(op for b in blocks[:2] for op in b)
+        assert sum(n for op, n in first.items() if op.startswith("v_") and not op.startswith("v_mfma")) <= 24, name
+        ops = collections.Counter(op for b in blocks[2:] for op in b)
         valu = sum(n for op, n in ops.items() if op.startswith("v_") and not op.startswith("v_mfma"))
         mfma = sum(n for op, n in ops.items() if op.startswith("v_mfma"))
-        # (the few that remain are address increments of LDS reads whose offsets exceed the immediate field)
         assert valu <= 6 and valu * 16 <= mfma, "%s: %d vector-ALU instructions among %d MFMAs" % (name, valu, mfma)
+        # no register is cleared with moves: the first MFMA into every accumulator takes the constant 0 instead
+        assert len(re.findall(r"v_mfma_f64_16x16x4_f64 v\[\d+:\d+\], v\[\d+:\d+\], v\[\d+:\d+\], 0\b", k["body"])) >= (bm // 32) * (bn // 32), name
         # operand fetches are amortised over the wave tile: fewer LDS reads than MFMAs even for the smallest one
         lds_reads = sum(n for op, n in ops.items() if op.startswith("ds_read"))
         assert lds_reads < mfma and ops["s_barrier"] >= 1, name
