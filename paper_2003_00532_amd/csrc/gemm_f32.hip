@@ -11,7 +11,7 @@ namespace {
 // two precisions behave alike (at 8192^3 the float kernels reach 95.2 / 93.4 / 94.5 / 95.7 % of the FP32 peak with the
 // 128x128 / 64x64 / 128x64 / 64x128 tiles).  What was measured in float is the outcome: over the 17 shapes of
 // `bench.py --selection-study --dtype f32` the variant chosen with these parameters is 1.2 % slower than the best
-// variant on average (largest: 2304^3, 9.7 %).
+// variant on average on one machine of the pool and 1.6 % on another (largest: 2304^3, 9.7 to 13.4 %).
 const Variant kVariants[] = {
     {"naive", 0, 0, 0.0, 1, 0.0},
     {"mfma_128x128x32", 128, 128, 0.955, 2, 286.0},
