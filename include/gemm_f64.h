@@ -69,7 +69,13 @@ enum {
  * whenever every partial sum is exact (e.g. small-integer data) and within
  * 1e-13 * sum_k |a_ik * b_kj| elementwise otherwise.  The zero padding the
  * kernel uses for ragged K is applied to both operands, so a live Inf or NaN
- * never meets a padded zero.
+ * never meets a padded zero.  The matrix unit returns sums of products that are
+ * themselves below the normal range (operands around 2^-540) as signed zeros;
+ * subnormal values of C are kept.  The one rounded addition per element that
+ * updates C is performed by the kernel's lanes or, for large problems in
+ * ordinary device memory, by the memory system: the same bits either way (see
+ * gemm_f64_set_epilogue_mode, the only process-wide state in the library, a
+ * diagnostic that defaults to automatic).
  *
  * Errors: a negative code from the enum above; no exception, no errno.
  */
