@@ -73,7 +73,7 @@ enum {
  * themselves below the normal range (operands around 2^-540) as signed zeros;
  * subnormal values of C are kept.  The one rounded addition per element that
  * updates C is performed by the kernel's lanes or, for large problems in
- * ordinary device memory, by the memory system: the same bits either way (see
+ * ordinary memory of the same GPU, by the memory system: the same bits either way (see
  * gemm_f64_set_epilogue_mode, the only process-wide state in the library, a
  * diagnostic that defaults to automatic).
  *
@@ -344,8 +344,9 @@ int gemm_f64_device_peak(int *compute_units, int *clock_khz, double *fp64_mfma_t
  * loads, adds and stores its elements, or it sends its sums to the memory system as floating-point additions without
  * return value (each element of C belongs to exactly one lane, so this is the same single rounding, and the order of
  * the additions is irrelevant).  The second form frees a workgroup's registers one memory latency earlier and is what
- * the library picks when K >= 256, C has at least 2^20 elements and C is ordinary device memory.
- *   mode 0  automatic (the default);  1  always load, add, store;  2  additions in memory whenever C is device memory.
+ * the library picks when K >= 256, C has at least 2^20 elements and C is ordinary device memory of the GPU the call
+ * runs on.
+ *   mode 0  automatic (the default);  1  always load, add, store;  2  additions in memory whenever C is such memory.
  * Returns the previous mode, or GEMM_F64_ERR_DIM for any other value.
  */
 int gemm_f64_set_epilogue_mode(int mode);

@@ -39,6 +39,14 @@ constexpr double kLoneTileSlots = 96.0;
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Grid of the element-wise kernels (256 threads a block, each striding over the elements): one block per 256 elements
+// up to 2^22 blocks; the runtime refuses launches of 2^32 threads or more, and C may well have more elements.
+inline unsigned elementwise_blocks(int64_t elements)
+{
+    const int64_t blocks = ceil_div(elements, 256), cap = (int64_t)1 << 22;
+    return (unsigned)(blocks < cap ? blocks : cap);
+}
+
 // A 32-wide panel exists only for an operand whose k index is contiguous in memory (A as given, B
 // stored transposed), so the 32-row variants need transa == 0 and the 32-column ones transb == 1.
 inline bool variant_available(const Variant &v, int transa, int transb)
@@ -326,8 +334,7 @@ hipError_t launch_variant(int variant, const Job<T> &j)
 template <typename T>
 hipError_t launch_naive(const Job<T> &j)
 {
-    const int64_t total = (int64_t)j.M * j.N;
-    const dim3 grid((unsigned)ceil_div(total, 256)), block(256);
+    const dim3 grid(elementwise_blocks((int64_t)j.M * j.N)), block(256);
     hipLaunchKernelGGL(gemm_naive_kernel<T>, grid, block, 0, j.stream, j.M, j.N, j.K, j.alpha, j.A, j.transa ? 1 : j.lda,
                        j.transa ? j.lda : 1, j.B, j.transb ? 1 : j.ldb, j.transb ? j.ldb : 1, j.beta, j.C, j.ldc, (int64_t)1);
     return hipGetLastError();
@@ -336,8 +343,7 @@ hipError_t launch_naive(const Job<T> &j)
 template <typename T>
 hipError_t launch_scale(int M, int N, T beta, T *C, int64_t rsc, int64_t csc, hipStream_t stream)
 {
-    const int64_t total = (int64_t)M * N;
-    const dim3 grid((unsigned)ceil_div(total, 256)), block(256);
+    const dim3 grid(elementwise_blocks((int64_t)M * N)), block(256);
     hipLaunchKernelGGL(scale_c_kernel<T>, grid, block, 0, stream, M, N, beta, C, rsc, csc);
     return hipGetLastError();
 }
@@ -351,7 +357,8 @@ hipError_t launch_scale(int M, int N, T beta, T *C, int64_t rsc, int64_t csc, hi
 // 4.12 ms, K = 1024 8.06 -> 7.96 ms; but K = 128 1.42 -> 1.77 ms, because the additions themselves take 1.64 ms for
 // 16384^2 elements (load and store: 0.88 ms) and must fit under the MFMA time, which they do from K = 242 upwards.
 // Hardware floating-point additions in memory are only defined for ordinary device memory (not for host memory
-// mapped into the device, nor managed memory), so the owner of C is asked first; single precision keeps the first
+// mapped into the device, nor managed memory) and are only used on the memory of the GPU that runs the kernel, so the
+// owner of C is asked first; single precision keeps the first
 // form (its additions in memory do not honour denormals).
 enum { kEpilogueAuto = 0, kEpilogueLoadStore = 1, kEpilogueInMemory = 2 };
 inline std::atomic<int> g_epilogue_mode{kEpilogueAuto};   // a diagnostic switch, see gemm_f64_set_epilogue_mode
@@ -364,11 +371,14 @@ bool accumulate_in_memory(int64_t M, int64_t N, int64_t K, T alpha, T beta, cons
     if (mode == kEpilogueLoadStore) return false;
     if (mode == kEpilogueAuto && (K < 256 || M * N < ((int64_t)1 << 20))) return false;
     hipPointerAttribute_t attr;
-    if (hipPointerGetAttributes(&attr, C) != hipSuccess) {
+    int dev = -1;
+    if (hipPointerGetAttributes(&attr, C) != hipSuccess || hipGetDevice(&dev) != hipSuccess) {
         (void)hipGetLastError();
         return false;
     }
-    return attr.type == hipMemoryTypeDevice;
+    // the memory of the device that runs the kernel: additions sent to a peer's memory cross a link that need not
+    // carry them
+    return attr.type == hipMemoryTypeDevice && attr.device == dev;
 }
 
 inline int current_cu_count()
@@ -425,7 +435,7 @@ int gemm_ex(const Variant *variants, int count, int transa, int transb, int64_t 
             err = launch_variant<T>(variant, job);
             if (err != hipSuccess) return GEMM_F64_ERR_LAUNCH;
             // second step: C <- alpha * (sum of the slabs, in order) + beta * C
-            const dim3 grid((unsigned)ceil_div(M * N, 256)), block(256);
+            const dim3 grid(elementwise_blocks(M * N)), block(256);
             hipLaunchKernelGGL(split_k_reduce_kernel<T>, grid, block, 0, stream, m, n, plan.splits, alpha, slabs, beta, C, ldc);
             return hipGetLastError() == hipSuccess ? GEMM_F64_OK : GEMM_F64_ERR_LAUNCH;
         }

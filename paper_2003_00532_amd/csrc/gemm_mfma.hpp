@@ -829,15 +829,17 @@ __global__ void __launch_bounds__(256)
 gemm_naive_kernel(int M, int N, int K, T alpha, const T *__restrict__ A, int64_t rsa, int64_t csa, const T *__restrict__ B,
                   int64_t rsb, int64_t csb, T beta, T *__restrict__ C, int64_t rsc, int64_t csc)
 {
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (int64_t)M * N) return;
-    const int i = (int)(idx / N), j = (int)(idx % N);
-    const T *a = A + (int64_t)i * rsa, *b = B + (int64_t)j * csb;
-    T acc = T(0);
-    for (int k = 0; k < K; ++k) acc += a[k * csa] * b[k * rsb];
-    const bool read_c = beta != T(0);
-    T *c = C + (int64_t)i * rsc + (int64_t)j * csc;
-    *c = scaled_update(alpha, acc, beta, read_c ? *c : T(0), read_c);
+    // the grid may be smaller than the matrix (the runtime limits a launch to 2^32 threads): each thread strides on
+    const int64_t total = (int64_t)M * N, step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += step) {
+        const int i = (int)(idx / N), j = (int)(idx % N);
+        const T *a = A + (int64_t)i * rsa, *b = B + (int64_t)j * csb;
+        T acc = T(0);
+        for (int k = 0; k < K; ++k) acc += a[k * csa] * b[k * rsb];
+        const bool read_c = beta != T(0);
+        T *c = C + (int64_t)i * rsc + (int64_t)j * csc;
+        *c = scaled_update(alpha, acc, beta, read_c ? *c : T(0), read_c);
+    }
 }
 
 // C <- beta * C (all zeros when beta is zero, whatever C held): what is left of the operation when
@@ -845,11 +847,12 @@ gemm_naive_kernel(int M, int N, int K, T alpha, const T *__restrict__ A, int64_t
 template <typename T>
 __global__ void __launch_bounds__(256) scale_c_kernel(int M, int N, T beta, T *__restrict__ C, int64_t rsc, int64_t csc)
 {
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (int64_t)M * N) return;
-    const int i = (int)(idx / N), j = (int)(idx % N);
-    T *p = C + (int64_t)i * rsc + (int64_t)j * csc;
-    *p = (beta != T(0)) ? beta * *p : T(0);
+    const int64_t total = (int64_t)M * N, step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += step) {
+        const int i = (int)(idx / N), j = (int)(idx % N);
+        T *p = C + (int64_t)i * rsc + (int64_t)j * csc;
+        *p = (beta != T(0)) ? beta * *p : T(0);
+    }
 }
 
 // The second step of a split K: C <- alpha * (W_0 + W_1 + ... + W_{S-1}) + beta * C, the slabs W_p (M x N, dense)
@@ -858,15 +861,15 @@ template <typename T>
 __global__ void __launch_bounds__(256)
 split_k_reduce_kernel(int M, int N, int splits, T alpha, const T *__restrict__ W, T beta, T *__restrict__ C, int64_t ldc)
 {
-    const int64_t total = (int64_t)M * N;
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    T s = W[idx];
-    for (int p = 1; p < splits; ++p) s += W[p * total + idx];
-    const int i = (int)(idx / N), j = (int)(idx % N);
-    const bool read_c = beta != T(0);
-    const T c = read_c ? C[(int64_t)i * ldc + j] : T(0);
-    C[(int64_t)i * ldc + j] = scaled_update(alpha, s, beta, c, read_c);
+    const int64_t total = (int64_t)M * N, step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += step) {
+        T s = W[idx];
+        for (int p = 1; p < splits; ++p) s += W[p * total + idx];
+        const int i = (int)(idx / N), j = (int)(idx % N);
+        const bool read_c = beta != T(0);
+        const T c = read_c ? C[(int64_t)i * ldc + j] : T(0);
+        C[(int64_t)i * ldc + j] = scaled_update(alpha, s, beta, c, read_c);
+    }
 }
 
 // The second step of a tail split (see TailSplit): for each of the last `tiles` tiles of the grouped order,

@@ -45,6 +45,53 @@ def test_c_larger_than_4_gib(gpu_device):
     assert bool(torch.isnan(dC[:, N:]).all()), "C padding was written"
 
 
+def test_c_with_more_than_2_to_the_32_elements(gpu_device):
+    # 65600^2 = 4.3e9 elements (34 GB): element indices of C pass 2^32, and one block per 256 elements would be more
+    # threads than a launch may have.  Data are small integers, so every result is exact: the whole of C is compared
+    # with the exact integer product computed on the device a block of rows at a time, sampled rows with the oracle.
+    free, _ = torch.cuda.mem_get_info()
+    if free < 60 * 2 ** 30:
+        pytest.skip("needs 60 GB of free device memory")
+    M = N = 65600
+    K = 8
+    dA, dB = _device_ints(11, M, K, K), _device_ints(12, K, N, N)
+    dC = torch.empty((M, N), dtype=torch.float64, device=DEV)
+    cols = torch.arange(N, device=DEV)
+    step = 4096
+
+    def c_in(r0, r1):
+        rows = torch.arange(r0, r1, device=DEV)
+        return ((rows[:, None] + cols[None, :]) % 7 - 3).double()
+
+    for r0 in range(0, M, step):
+        dC[r0:r0 + step] = c_in(r0, min(M, r0 + step))
+    # no product: C <- 2 C by the scaling kernel alone
+    binding.gemm_f64_general(0, 0, M, N, K, 0.0, dA, K, dB, N, 2.0, dC, N)
+    torch.cuda.synchronize()
+    for r0 in range(0, M, step):
+        assert torch.equal(dC[r0:r0 + step], 2.0 * c_in(r0, min(M, r0 + step))), "scaling differs in rows from %d" % r0
+    # the paper's operation on top of it
+    binding.gemm_f64(M, N, K, dA, K, dB, N, dC, N)
+    torch.cuda.synchronize()
+    for r0 in range(0, M, step):
+        r1 = min(M, r0 + step)
+        assert torch.equal(dC[r0:r1], 2.0 * c_in(r0, r1) + dA[r0:r1] @ dB), "product differs in rows from %d" % r0
+    rows = synth.sample_rows(M, 16, seed=3)
+    idx = torch.from_numpy(rows).to(DEV)
+    want = np.ascontiguousarray((2.0 * ((rows[:, None] + np.arange(N)[None, :]) % 7 - 3)).astype(np.float64))
+    oracle.gemm_f64_ref(np.ascontiguousarray(dA[idx].cpu().numpy()), dB.cpu().numpy(), want)
+    pins.assert_bitwise(dC[idx].cpu().numpy(), want, "rows of a C of 4.3e9 elements")
+    # the untiled kernel strides over the elements in the same way (a smaller K: one thread per element is slow)
+    dC2 = dC[:, :].view(M, N)
+    for r0 in range(0, M, step):
+        dC2[r0:r0 + step] = c_in(r0, min(M, r0 + step))
+    binding.gemm_f64_ex(M, N, 2, dA, K, dB, N, dC2, N, variant=0)
+    torch.cuda.synchronize()
+    for r0 in range(0, M, step):
+        r1 = min(M, r0 + step)
+        assert torch.equal(dC2[r0:r1], c_in(r0, r1) + dA[r0:r1, :2] @ dB[:2]), "untiled kernel differs in rows from %d" % r0
+
+
 @pytest.mark.parametrize("shape", [(1, 300000, 70), (300000, 1, 70), (3, 5, 100003), (2, 70001, 2), (70001, 2, 2),
                                    (100000, 3, 7), (5, 33, 1)])
 def test_extreme_aspect_ratios(gpu_device, shape):
