@@ -98,6 +98,12 @@ def main():
         print("  %-34s mean %8.2f  p10 %8.2f  p50 %8.2f  p90 %8.2f us" % (name, d.mean(), np.percentile(d, 10), np.percentile(d, 50), np.percentile(d, 90)))
 
     row("entry -> first stage barrier", first_barrier - entry)
+    late = entry > 5.0
+    if late.any() and (~late).any():
+        # a workgroup that starts on a busy compute unit is the youngest wave on its SIMDs, and the SIMD serves older ones first
+        print("    of which the %d workgroups that start in the first 5 us: mean %.2f us; the %d that start later, beside workgroups "
+              "already in their K loops: mean %.2f us" % ((~late).sum(), (first_barrier - entry)[~late].mean(), late.sum(),
+                                                            (first_barrier - entry)[late].mean()))
     row("K loop", k_end - first_barrier)
     row("epilogue (C update)", exit_ - k_end)
     row("whole life", exit_ - entry)
