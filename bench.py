@@ -168,10 +168,16 @@ def other_workloads(gemm_ex, choose, variant_name, np_dtype, peak, seed, stream,
                      "tflops": round(w.flops / (ms * 1e-3) / 1e12, 3), "frac": round(w.flops / (ms * 1e-3) / 1e12 / peak, 4),
                      "back_to_back_ms": round(b2b, 5), "back_to_back_tflops": round(w.flops / (b2b * 1e-3) / 1e12, 3),
                      "back_to_back_frac": round(w.flops / (b2b * 1e-3) / 1e12 / peak, 4)}
-        # the same workload through the entry point that takes a workspace, when its plan would use one
         from paper_2003_00532_amd import binding as _b
         import numpy as np
         f32w = np_dtype == np.float32
+        # HBM-side bytes per launch from the tracked counter summary of this kernel and workload, if there is one
+        traffic, source = traffic_from_profile("s" if f32w else "d", out[name]["kernel_variant"], name, _b.gemm_f64_build_id())
+        if traffic is not None:
+            out[name]["traffic"] = traffic
+            out[name]["algorithmic_bytes_per_launch"] = w.algorithmic_bytes * np.dtype(np_dtype).itemsize / 8.0
+            out[name]["traffic_source"] = {"file": source.get("file"), "same_build": source.get("same_build")}
+        # the same workload through the entry point that takes a workspace, when its plan would use one
         ws_bytes = (_b.gemm_f32_split_k_workspace_bytes if f32w else _b.gemm_f64_split_k_workspace_bytes)(0, 0, w.M, w.N, w.K, cus)
         if ws_bytes > 0:
             general_ws = _b.gemm_f32_general_ws if f32w else _b.gemm_f64_general_ws
