@@ -37,6 +37,14 @@ inline double few_resident_penalty(int resident_now, int resident_full)
 // writing C), in MFMA issue slots; it only matters for problems of a few tiles.
 constexpr double kLoneTileSlots = 96.0;
 
+// What a launch costs once, whatever its length: at its start every workgroup is in its prologue and at its end the
+// last ones are in their epilogues with nothing to hide under, and both grow with the outputs of a tile.  In MFMA issue
+// slots per 4096 outputs of a tile (64 x 64: 8 us in double).  Fitted on the measured table of every variant on 17
+// shapes (ten tables from three machines and both precisions): the mean regret of the choice falls from 1.3 % to 0.4 %,
+// the largest from 15 % to 6 %, and the fit is flat from 250 to 600.
+constexpr double kLaunchExposureSlots = 300.0;
+inline double launch_exposure(const Variant &var) { return kLaunchExposureSlots * (double)(var.bm * var.bn) / 4096.0; }
+
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Grid of the element-wise kernels (256 threads a block, each striding over the elements): one block per 256 elements
@@ -60,8 +68,9 @@ inline bool variant_available(const Variant &v, int transa, int transb)
 // each of its four waves (BM/32) * (BN/32) MFMAs per k-step at the variant's measured efficiency, plus
 // what is not hidden of its prologue and epilogue (a measured number of slots per variant: it grows with
 // the outputs per tile and is larger where fewer workgroups share a compute unit).  Workgroups are spread over the compute
-// units, so the throughput-bound makespan is ceil(tiles / CUs) such tiles: a smaller tile wastes less at
-// the edges and balances better but runs its inner loop a little less efficiently.  The makespan cannot
+// units, so the throughput-bound makespan is ceil(tiles / CUs) such tiles, plus what the start and the end of a launch
+// expose (launch_exposure): a smaller tile wastes less at the edges, balances better and exposes less, but runs its
+// inner loop a little less efficiently.  The makespan cannot
 // be shorter than the time one tile needs on its own (the MFMA chain of one wave plus a fixed start-up
 // and write-back cost): that floor is what counts when there are fewer tiles than compute units.
 // Variant 0 (untiled) is never chosen.
@@ -72,7 +81,7 @@ inline double variant_cost(const Variant &var, int64_t M, int64_t N, int64_t K, 
     const int64_t per_cu = ceil_div(tiles, num_cu);
     const double eff = var.efficiency * few_resident_penalty(per_cu < var.resident ? (int)per_cu : var.resident, var.resident);
     const double wave_chain = (double)(var.bm / 32) * (var.bn / 32);   // MFMAs per k-step in one wave
-    const double throughput = (double)per_cu * (wave_chain * ksteps / eff + var.overhead);
+    const double throughput = (double)per_cu * (wave_chain * ksteps / eff + var.overhead) + launch_exposure(var);
     const double floor_alone = wave_chain * ksteps + kLoneTileSlots;
     return throughput > floor_alone ? throughput : floor_alone;
 }
@@ -155,7 +164,9 @@ constexpr int64_t kMaxExtent = (int64_t)INT32_MAX - 128;
 // tile while the others idle (2088 x 2049 x 2047 with 64 x 64 tiles: 1089 tiles on 1024 slots, the last 65 tiles run
 // alone).  With a workspace the k range of just those last tiles is cut into S slices so that tail * S units fill one
 // round of slots, each a fraction 1/S of a tile long; their slabs are added in a second, small launch.  The plan prices
-// every variant that way with the model of variant_cost and keeps the cheapest if it beats the unsplit choice by 3 %.
+// every variant that way with the model of variant_cost and keeps the cheapest if it beats the unsplit choice (the second
+// step is priced at more than twice what it measures, which is margin enough: of fifteen shapes with partial rounds the nine
+// that get a plan this way all gain, 1.2 to 9 points of the peak).
 inline Plan plan_tail_split(const Variant *variants, int count, int transa, int transb, int64_t M, int64_t N, int64_t K,
                             int num_cu, int elem_bytes, int64_t workspace_bytes, const Plan &unsplit, double unsplit_cost)
 {
@@ -163,7 +174,7 @@ inline Plan plan_tail_split(const Variant *variants, int count, int transa, int 
     if (M <= 0 || N <= 0 || K <= 0 || workspace_bytes <= 0) return best;
     const int bk = 8 * (16 / elem_bytes);
     const double slot_seconds = (elem_bytes == 8 ? 64.0 : 32.0) / 2.4e9;
-    double best_cost = unsplit_cost * 0.97;
+    double best_cost = unsplit_cost;
     const int64_t nk = ceil_div(K, bk);
     for (int v = 1; v < count; ++v) {
         const Variant &var = variants[v];
@@ -186,7 +197,8 @@ inline Plan plan_tail_split(const Variant *variants, int count, int transa, int 
         const double tile_cost = wave_chain * (double)ceil_div(K, 4) / var.efficiency + var.overhead;
         const double unit_cost = wave_chain * (double)(chunk_stages * bk / 4) / var.efficiency + var.overhead;
         const double reduce = ((double)(slices + 2) * tail * var.bm * var.bn * elem_bytes / 2.5e12 + 4e-6) / slot_seconds;
-        const double cost = (double)(rounds * var.resident) * tile_cost + (double)ceil_div(tail * slices, num_cu) * unit_cost + reduce;
+        const double cost = (double)(rounds * var.resident) * tile_cost + (double)ceil_div(tail * slices, num_cu) * unit_cost + reduce +
+                            0.5 * launch_exposure(var);   // the start only: the end of such a launch is its short units
         if (cost < best_cost) {
             best_cost = cost;
             best = Plan{v, 1, (int)K, (int)tail, (int)slices, (int)(chunk_stages * bk)};
