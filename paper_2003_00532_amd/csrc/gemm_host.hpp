@@ -113,7 +113,7 @@ inline int choose_variant(const Variant *variants, int count, int transa, int tr
 // of the shape, the CU count and the workspace on offer: for each S the cost of the first step by the
 // model above, plus the second step as (S + 2) M N elements moved at about 2.5 TB/s and a launch of 4 us,
 // converted to the model's unit (more than twice what the second step measures, which is the margin: of eighteen
-// shapes of few tiles the ten that get a plan this way all gain, up to a factor of two).
+// shapes of few tiles ten get a plan this way, of which nine gain, up to a factor of two, and one is even).
 struct Plan {
     int variant;
     int splits;     // 1: no split
