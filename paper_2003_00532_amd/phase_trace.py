@@ -122,6 +122,18 @@ def main():
         row("exit -> next entry, same compute unit", np.concatenate(gaps))
     print("  compute units seen %d; workgroups resident per compute unit on average %.2f, of which inside their K loop %.2f"
           % (len(keys), (exit_ - entry).sum() / (span * len(keys)), (k_end - first_barrier).sum() / (span * len(keys))))
+    # the ragged end: from the moment the chip holds fewer than 97 % of its usual number of workgroups
+    grid = np.linspace(0.0, span, 400)
+    resident = np.array([((entry <= g) & (exit_ > g)).sum() for g in grid])
+    steady = float(np.median(resident[50:300]))
+    if steady > 0:
+        full = np.where(resident >= 0.97 * steady)[0]
+        drain_from = grid[full.max()] if len(full) else 0.0
+        unused = (steady - resident[grid >= drain_from]).clip(min=0).sum() * (grid[1] - grid[0]) / (steady * span)
+        last_exit = np.array([exit_[cu_key == k].max() for k in keys])
+        print("  the end: %d workgroups resident in the steady state; the chip empties over the last %.1f us (%.1f %% of the launch), "
+              "%.1f %% of the launch's slot-time is unused there; a compute unit's last exit is %.1f us before the end on average"
+              % (steady, span - drain_from, 100 * (span - drain_from) / span, 100 * unused, (span - last_exit).mean()))
     mhz = (t[:, 2] - t[:, 1]) / ((t[:, 5] - t[:, 0]) * 0.01)
     print("  shader clock over workgroup lifetimes: mean %.0f MHz (p10 %.0f, p90 %.0f)" % (mhz.mean(), np.percentile(mhz, 10), np.percentile(mhz, 90)))
 
