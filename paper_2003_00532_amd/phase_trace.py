@@ -135,6 +135,10 @@ def main():
               "%.1f %% of the launch's slot-time is unused there; a compute unit's last exit is %.1f us before the end on average"
               % (steady, span - drain_from, 100 * (span - drain_from) / span, 100 * unused, (span - last_exit).mean()))
     mhz = (t[:, 2] - t[:, 1]) / ((t[:, 5] - t[:, 0]) * 0.01)
+    # the eight XCDs one by one: workgroup b runs on XCD b % 8, so each has the same number of tiles whatever its speed
+    print("  per XCD (workgroups | mean K loop us | last exit us | shader clock MHz): " +
+          "  ".join("%d: %d | %.1f | %.1f | %.0f" % (x, (xcc == x).sum(), (k_end - first_barrier)[xcc == x].mean(), exit_[xcc == x].max(),
+                                                    mhz[xcc == x].mean()) for x in np.unique(xcc)))
     print("  shader clock over workgroup lifetimes: mean %.0f MHz (p10 %.0f, p90 %.0f)" % (mhz.mean(), np.percentile(mhz, 10), np.percentile(mhz, 90)))
 
 
