@@ -136,9 +136,15 @@ def main():
               % (steady, span - drain_from, 100 * (span - drain_from) / span, 100 * unused, (span - last_exit).mean()))
     mhz = (t[:, 2] - t[:, 1]) / ((t[:, 5] - t[:, 0]) * 0.01)
     # the eight XCDs one by one: workgroup b runs on XCD b % 8, so each has the same number of tiles whatever its speed
-    print("  per XCD (workgroups | mean K loop us | last exit us | shader clock MHz): " +
-          "  ".join("%d: %d | %.1f | %.1f | %.0f" % (x, (xcc == x).sum(), (k_end - first_barrier)[xcc == x].mean(), exit_[xcc == x].max(),
-                                                    mhz[xcc == x].mean()) for x in np.unique(xcc)))
+    def own_peak(x):
+        # what the XCD's share of the flops took, against the FP64 matrix rate of its compute units at the clock it held
+        sel = xcc == x
+        cus_x = len(np.unique(cu_key[sel]))
+        return 100.0 * (w.flops * sel.sum() / blocks) / (exit_[sel].max() * 1e-6) / (cus_x * 4 * 32 * mhz[sel].mean() * 1e6)
+
+    print("  per XCD (workgroups | mean K loop us | last exit us | shader clock MHz | % of its own peak at that clock): " +
+          "  ".join("%d: %d | %.1f | %.1f | %.0f | %.1f" % (x, (xcc == x).sum(), (k_end - first_barrier)[xcc == x].mean(),
+                                                           exit_[xcc == x].max(), mhz[xcc == x].mean(), own_peak(x)) for x in np.unique(xcc)))
     print("  shader clock over workgroup lifetimes: mean %.0f MHz (p10 %.0f, p90 %.0f)" % (mhz.mean(), np.percentile(mhz, 10), np.percentile(mhz, 90)))
 
 
